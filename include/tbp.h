@@ -1,0 +1,181 @@
+/*
+ * tbp.h - C ABI of the two-stage-backpropagation (2BP) stage library for AMD MI355X (gfx950).
+ *
+ * One object, a "stage", is one pipeline stage of a LLaMa-like decoder stack (RMSNorm, rotary
+ * embedding, causal attention, SwiGLU MLP, no linear bias: the paper's Transformer-7b, Section 3.2).
+ * Its backward pass is split as the paper's Section 3.1 defines:
+ *   backward-p1  gradient w.r.t. the output of the preceding layer (input gradients), per micro-batch;
+ *   backward-p2  gradient w.r.t. the layer parameters, deferred, computed later from what p1 left behind.
+ *
+ * General rules for every entry point
+ *   - Plain C.  No exceptions cross the boundary.  Every function returns a tbp_status; on failure
+ *     tbp_last_error() gives a human-readable reason (thread-local, valid until the next call).
+ *   - "device" pointers are HIP device addresses valid on the current device; "host" pointers are
+ *     ordinary process memory.  The library never allocates or frees device memory: weights,
+ *     gradients, the stash arena, inputs, outputs and the stream all belong to the caller and must
+ *     outlive the calls (and, for the arena / weights / gradients, the stage) that use them.
+ *   - All device work is enqueued on the hipStream_t passed as `void* stream` (NULL = the null
+ *     stream) and the call returns without synchronising.  Device-side failures detectable at
+ *     launch time are reported as TBP_EDEVICE.
+ *   - Argument errors are detected on the host before anything is launched (TBP_EINVAL /
+ *     TBP_ESTATE / TBP_ENOMEM): a failing call launches nothing and changes no state.
+ *   - Layouts: activations and gradients are token-major, row-major [tokens, width] with
+ *     tokens = micro_batch * seq and sequence b in rows b*seq .. (b+1)*seq-1.  Weights are
+ *     row-major [in, out] so that Y = X W, dX = dY W^T, dW = X^T dY.  q/k/v projections are one
+ *     fused matrix [d_model, 3*d_model] (column blocks q, k, v); gate/up are fused [d_model, 2*d_ffn]
+ *     (column blocks gate, up).  Head h owns columns h*head_dim .. (h+1)*head_dim-1.
+ *   - Storage type: TBP_BF16 (bfloat16 storage, fp32 accumulation, MFMA matrix cores) or TBP_F32
+ *     (fp32 everywhere).  Parameter gradients are always fp32.
+ *   - Size limits (TBP_EINVAL otherwise): bf16 needs d_model, d_ffn, head_dim and seq to be multiples
+ *     of 8; d_model <= 8192 (bf16) or 4096 (f32); seq <= 4096; head_dim even.
+ */
+#ifndef TBP_H
+#define TBP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tbp_stage tbp_stage; /* opaque; host-side bookkeeping only */
+
+typedef enum {
+  TBP_OK = 0,
+  TBP_EINVAL = 1,  /* bad argument (null pointer, size outside the limits, bad micro-batch set) */
+  TBP_ESTATE = 2,  /* call order violates the per-micro-batch state machine */
+  TBP_ENOMEM = 3,  /* arena too small, or no free activation slot */
+  TBP_EDEVICE = 4  /* HIP reported an error at launch */
+} tbp_status;
+
+typedef enum { TBP_F32 = 0, TBP_BF16 = 1 } tbp_dtype;
+
+/* How backward-p2 walks a set of micro-batches (Section 3.2, Figure 2; Section 4.4, Table 3):
+ *   LOOP     one weight-gradient product per micro-batch, accumulated in fp32;
+ *   KCONCAT  the micro-batches are treated as one batch concatenated over the batch dimension,
+ *            i.e. one product whose contraction length is n_mbs * tokens.  The stash keeps each
+ *            tensor's micro-batches in consecutive rows of one slab, so no copy is made; the set
+ *            must therefore be ascending consecutive indices (TBP_EINVAL otherwise). */
+typedef enum { TBP_P2_LOOP = 0, TBP_P2_KCONCAT = 1 } tbp_p2_mode;
+
+typedef struct {
+  int32_t n_layers;
+  int32_t d_model;
+  int32_t n_heads;          /* 0 => MLP-only blocks: x + Wd(silu(g)*u), [g,u] = RMSNorm(x) Wgu */
+  int32_t head_dim;         /* n_heads * head_dim must equal d_model when n_heads > 0 */
+  int32_t d_ffn;
+  int32_t seq;
+  int32_t micro_batch;      /* sequences per micro-batch */
+  int32_t max_microbatches; /* micro-batch indices are 0 .. max_microbatches-1 (rows of every slab) */
+  int32_t act_slots;        /* micro-batches that may be between forward and p1 at once;
+                               0 => max_microbatches.  Sizes the forward->p1 part of the stash. */
+  int32_t causal;           /* 1: query i attends to keys j <= i */
+  int32_t dtype;            /* tbp_dtype */
+  float rms_eps;            /* added to the mean square inside the square root */
+  float rope_base;
+} tbp_config;
+
+/* Per-layer arrays (host arrays of length n_layers holding DEVICE pointers).  The w_* / g* arrays hold
+ * tensors of the storage type; the d* arrays hold fp32 gradients of the same shapes.
+ * For MLP-only stages the attention entries (w_qkv, w_o, g1 and their gradients) may be NULL. */
+typedef struct {
+  const void* const* w_qkv; /* [d_model, 3 d_model] */
+  const void* const* w_o;   /* [d_model, d_model]   */
+  const void* const* g1;    /* [d_model] gain of the pre-attention RMSNorm */
+  const void* const* w_gu;  /* [d_model, 2 d_ffn]   */
+  const void* const* w_d;   /* [d_ffn, d_model]     */
+  const void* const* g2;    /* [d_model] gain of the pre-MLP RMSNorm */
+  float* const* dw_qkv;
+  float* const* dw_o;
+  float* const* dg1;
+  float* const* dw_gu;
+  float* const* dw_d;
+  float* const* dg2;
+} tbp_params;
+
+/* Bytes held by the stash (Section 4.2: linear layers keep their input activation and output
+ * derivative until p2; functional operations release their activations in p1). */
+typedef struct {
+  size_t w_stash_bytes;    /* slabs that live until p2: linear-layer inputs and output derivatives */
+  size_t a_stash_bytes;    /* slots that live from forward to p1 only */
+  size_t workspace_bytes;  /* per-call scratch (never live between calls) */
+  size_t arena_bytes;      /* total the caller must provide (sum of the above plus alignment) */
+} tbp_stash_sizes;
+
+typedef struct {
+  size_t w_live_bytes;     /* bytes of p2 operands currently held */
+  size_t a_live_bytes;     /* bytes of forward->p1 activations currently held */
+  size_t high_water_bytes; /* maximum of w_live + a_live since creation or the last reset */
+} tbp_stash_stats;
+
+/* Size query.  Host pointers.  No device access. */
+tbp_status tbp_stash_query(const tbp_config* cfg, tbp_stash_sizes* out);
+
+/* Create a stage over a caller-provided device arena of at least arena_bytes (256-byte aligned).
+ * The pointer arrays inside `params` are copied; the tensors they point to are not. */
+tbp_status tbp_stage_create(const tbp_config* cfg, const tbp_params* params, void* arena_device,
+                            size_t arena_bytes, tbp_stage** out);
+void tbp_stage_destroy(tbp_stage* st);
+
+/* Forward of micro-batch mb (state EMPTY -> FWD): x_in [tokens, d_model] -> x_out, both device, storage
+ * type.  Fills the stash.  Needs a free activation slot (TBP_ENOMEM otherwise). */
+tbp_status tbp_stage_forward(tbp_stage* st, int mb, const void* x_in, void* x_out, void* stream);
+
+/* backward-p1 of micro-batch mb (state FWD -> P1_DONE), Section 3.1: dy = gradient w.r.t. the stage
+ * output, dx = gradient w.r.t. the stage input, device, storage type.  Leaves every linear layer's
+ * output derivative (and the per-micro-batch RMSNorm gain partials) in the stash and releases the
+ * micro-batch's activation slot. */
+tbp_status tbp_stage_backward_p1(tbp_stage* st, int mb, const void* dy, void* dx, void* stream);
+
+/* backward-p2 of a set of micro-batches, all in state P1_DONE (-> EMPTY), Sections 3.1 and 3.2:
+ * parameter gradients from the stash.  `mbs` is a host array.  accumulate != 0: gradients += result;
+ * accumulate == 0: gradients = result (for LOOP the first micro-batch of the set overwrites).
+ * Calling p1(mb) then p2({mb}, LOOP) reproduces unsplit backpropagation. */
+tbp_status tbp_stage_backward_p2(tbp_stage* st, const int* mbs, int n_mbs, int p2_mode, int accumulate,
+                                 void* stream);
+
+tbp_status tbp_stage_stash_stats(const tbp_stage* st, tbp_stash_stats* out);
+/* All micro-batches back to EMPTY, all slots free, high-water mark cleared.  Gradients untouched. */
+tbp_status tbp_stage_reset(tbp_stage* st);
+
+/* ---- single operations (the kernels the stage is made of), exposed for parity tests and roofline
+ * measurement.  All pointers device unless noted; dtype is a tbp_dtype; leading dimensions in elements. */
+
+/* C[M,N] (= or +=) alpha * op(A) op(B) (+ R).  layout: 0 = NN (A [M,K], B [K,N]), 1 = NT (A [M,K],
+ * B [N,K]: dX = dY W^T, Section 3.1), 2 = TN (A [K,M], B [K,N]: dW = X^T dY, Section 3.1).
+ * out_f32 != 0: C is fp32 (and may accumulate); else C has the storage type and R (optional,
+ * same shape and leading dimension as C) is added before rounding. */
+tbp_status tbp_gemm(int dtype, int layout, int M, int N, int K, float alpha, const void* A, int lda,
+                    const void* B, int ldb, void* C, int ldc, int out_f32, int accumulate, const void* R,
+                    void* stream);
+tbp_status tbp_rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, const void* g, void* y,
+                           void* stream);
+/* dx = resid + dL/dx of RMSNorm (resid may be NULL); dg_out [d] fp32 = sum_t dy x r (overwritten).
+ * scratch: device, >= tbp_rmsnorm_p1_scratch_bytes(d). */
+tbp_status tbp_rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
+                          const void* resid, void* dx, float* dg_out, void* scratch, void* stream);
+size_t tbp_rmsnorm_p1_scratch_bytes(int d);
+/* gu [rows, 2f] (gate | up) -> m [rows, f];  p1: dm [rows, f], gu -> dgu [rows, 2f]. */
+tbp_status tbp_swiglu_fwd(int dtype, int rows, int f, const void* gu, void* m, void* stream);
+tbp_status tbp_swiglu_p1(int dtype, int rows, int f, const void* dm, const void* gu, void* dgu, void* stream);
+/* Rotary embedding in place on n_heads heads starting at column 0 of x [rows, ld]; position = row % seq.
+ * inverse != 0 rotates by the negated angle (backward-p1).  table: device scratch of
+ * tbp_rope_table_bytes(seq, head_dim), filled by tbp_rope_table. */
+size_t tbp_rope_table_bytes(int seq, int head_dim);
+tbp_status tbp_rope_table(int seq, int head_dim, float base, void* table, void* stream);
+tbp_status tbp_rope(int dtype, int rows, int seq, int n_heads, int head_dim, int ld, const void* table,
+                    int inverse, void* x, void* stream);
+/* Row softmax of n_mat matrices [seq, seq]: scores fp32 -> P (storage type).  causal: columns j > i get
+ * probability 0.  p1: dS = P * (dP - rowsum(dP * P)), written over dP. */
+tbp_status tbp_softmax_fwd(int dtype, int n_mat, int seq, int causal, const float* scores, void* P, void* stream);
+tbp_status tbp_softmax_p1(int dtype, int n_mat, int seq, int causal, const void* P, void* dP_dS, void* stream);
+
+const char* tbp_last_error(void);
+/* Library version string (static storage). */
+const char* tbp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TBP_H */

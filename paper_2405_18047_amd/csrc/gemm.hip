@@ -1,0 +1,416 @@
+// GEMM kernels for gfx950 (MI355X).
+//
+// bf16 path: C = alpha * op(A) op(B) on the 32x32x16 bf16 MFMA instruction, fp32 accumulation.
+//   One workgroup = 4 wavefronts (2 x 2), block tile BM x BN x 64, double-buffered LDS.
+//   An operand whose contraction index is contiguous in memory ("KC": A of NN/NT, B of NT) is kept in
+//   LDS as [row][k] and read as 16-byte vectors; an operand whose contraction index is the slow,
+//   strided one ("KS": A of TN, B of NN/TN, i.e. both operands of dW = X^T dY) is kept as [k][row]
+//   exactly as it sits in memory and transposed on the way to the registers by the LDS
+//   transpose-read instruction (ds_read_b64_tr_b16), so no operand is ever transposed in HBM.
+//   Global loads are buffer loads whose out-of-range lanes are redirected past the end of the
+//   descriptor (they return zero), which handles ragged M, N and K without branches.
+// fp32 path: plain FMA tile kernel with generic strides (the fp32 configuration is tiny).
+#include "kernels.h"
+
+namespace tbp {
+
+typedef __bf16 bf16_t;
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+struct GemmParams {
+  const void* A; const void* B; void* C; const void* R;
+  long lda, ldb, ldc;
+  long sAo, sAi, sBo, sBi, sCo, sCi;
+  int M, N, K;
+  int batch_inner;
+  int tiles_m, tiles_n;
+  float alpha;
+  int accumulate;
+  int causal;
+  // fp32 kernel only: element strides of A(m,k) and B(k,n)
+  long sam, sak, sbk, sbn;
+};
+
+constexpr int BK = 64;
+constexpr unsigned kOob = 0x80000000u;     // byte offset beyond every descriptor: the load returns zero
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, 0x7fffffff, 0x00020000);
+}
+
+// Workgroup id -> (tile row, tile column).  Workgroups are handed to the 8 XCDs round-robin; the first
+// step makes each XCD own a contiguous range of the tile sequence (so its private L2 sees neighbouring
+// tiles), the second walks that sequence in groups of 8 tile rows so that concurrently running tiles
+// share A and B panels.
+__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int nt = tiles_m * tiles_n;
+  const int xcd = pid & 7, q = pid >> 3;
+  const int per = nt >> 3, rem = nt & 7;
+  int id = xcd * per + (xcd < rem ? xcd : rem) + q;
+  const int GROUP = 8;
+  const int width = GROUP * tiles_n;
+  const int grp = id / width;
+  const int first = grp * GROUP;
+  const int gsz = (tiles_m - first) < GROUP ? (tiles_m - first) : GROUP;
+  const int r = id - grp * width;
+  tm = first + r % gsz;
+  tn = r / gsz;
+}
+
+template <int BM, int BN, bool AKC, bool BKC, typename OutT>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
+  constexpr int WM = BM / 2, WN = BN / 2;       // per-wave tile
+  constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wave
+  constexpr int LDA_S = AKC ? (BK + 8) : (BM + 16);   // LDS row stride in elements
+  constexpr int LDB_S = BKC ? (BK + 8) : (BN + 16);
+  constexpr int A_ELEMS = AKC ? BM * LDA_S : BK * LDA_S;
+  constexpr int B_ELEMS = BKC ? BN * LDB_S : BK * LDB_S;
+  constexpr int NA = BM / 32, NB = BN / 32;     // 16-byte global loads per thread per K tile
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* sA[2] = {smem, smem + A_ELEMS + B_ELEMS};
+  bf16_t* sB[2] = {smem + A_ELEMS, smem + 2 * A_ELEMS + B_ELEMS};
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  int tm_i, tn_i;
+  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm_i, tn_i);
+  const int m0 = tm_i * BM, n0 = tn_i * BN;
+
+  int k_lo = 0, k_hi = p.K;
+  if (p.causal == CAUSAL_SKIP_UPPER) {
+    if (n0 > m0 + BM - 1) return;
+  } else if (p.causal == CAUSAL_K_END) {
+    k_hi = (m0 + BM < p.K) ? m0 + BM : p.K;
+  } else if (p.causal == CAUSAL_K_BEGIN) {
+    k_lo = m0;
+  }
+
+  const int z = blockIdx.z;
+  const int zo = z / p.batch_inner, zi = z - zo * p.batch_inner;
+  const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A) + zo * p.sAo + zi * p.sAi;
+  const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B) + zo * p.sBo + zi * p.sBi;
+
+  // ---- per-thread global -> LDS copy plan (byte offsets relative to the K-tile origin of each operand)
+  unsigned a_goff[NA], b_goff[NB];
+  int a_soff[NA], b_soff[NB];
+  int a_kidx[NA], b_kidx[NB];     // k index inside the tile that the load covers (first element)
+  if constexpr (AKC) {            // tile [BM rows][64 k]: 8 granules per row
+    const int gc = tid & 7;
+#pragma unroll
+    for (int i = 0; i < NA; i++) {
+      const int row = (tid >> 3) + 32 * i;
+      a_goff[i] = (m0 + row < p.M) ? (unsigned)((long)row * p.lda * 2 + gc * 16) : kOob;
+      a_soff[i] = row * LDA_S + gc * 8;
+      a_kidx[i] = gc * 8;
+    }
+  } else {                        // tile [64 k][BM cols]: BM/8 granules per row
+    constexpr int GPR = BM / 8, RSTEP = 256 / GPR;
+    const int gc = tid % GPR;
+#pragma unroll
+    for (int i = 0; i < NA; i++) {
+      const int kr = tid / GPR + RSTEP * i;
+      a_goff[i] = (m0 + gc * 8 < p.M) ? (unsigned)((long)kr * p.lda * 2 + gc * 16) : kOob;
+      a_soff[i] = kr * LDA_S + gc * 8;
+      a_kidx[i] = kr;
+    }
+  }
+  if constexpr (BKC) {
+    const int gc = tid & 7;
+#pragma unroll
+    for (int i = 0; i < NB; i++) {
+      const int row = (tid >> 3) + 32 * i;
+      b_goff[i] = (n0 + row < p.N) ? (unsigned)((long)row * p.ldb * 2 + gc * 16) : kOob;
+      b_soff[i] = row * LDB_S + gc * 8;
+      b_kidx[i] = gc * 8;
+    }
+  } else {
+    constexpr int GPR = BN / 8, RSTEP = 256 / GPR;
+    const int gc = tid % GPR;
+#pragma unroll
+    for (int i = 0; i < NB; i++) {
+      const int kr = tid / GPR + RSTEP * i;
+      b_goff[i] = (n0 + gc * 8 < p.N) ? (unsigned)((long)kr * p.ldb * 2 + gc * 16) : kOob;
+      b_soff[i] = kr * LDB_S + gc * 8;
+      b_kidx[i] = kr;
+    }
+  }
+  // origin of this block's panel at k = 0
+  const bf16_t* Ablk = AKC ? A + (long)m0 * p.lda : A + m0;
+  const bf16_t* Bblk = BKC ? B + (long)n0 * p.ldb : B + n0;
+  const long a_kstep = AKC ? 1 : p.lda;     // elements per unit of k
+  const long b_kstep = BKC ? 1 : p.ldb;
+
+  u32x4 ra[NA], rb[NB];
+  auto load_tile = [&](int k0) {
+    const int krem = k_hi - k0;             // valid k in this tile: [0, krem)
+    __amdgpu_buffer_rsrc_t rsA = make_rsrc(Ablk + (long)k0 * a_kstep);
+    __amdgpu_buffer_rsrc_t rsB = make_rsrc(Bblk + (long)k0 * b_kstep);
+#pragma unroll
+    for (int i = 0; i < NA; i++)
+      ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, a_kidx[i] < krem ? a_goff[i] : kOob, 0, 0);
+#pragma unroll
+    for (int i = 0; i < NB; i++)
+      rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsB, b_kidx[i] < krem ? b_goff[i] : kOob, 0, 0);
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < NA; i++) *reinterpret_cast<u32x4*>(sA[buf] + a_soff[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < NB; i++) *reinterpret_cast<u32x4*>(sB[buf] + b_soff[i]) = rb[i];
+  };
+
+  // ---- per-lane LDS read offsets of the MFMA operand fragments (elements, k-step 0, tile 0)
+  // KC: row = lane % 32, 8 consecutive k starting at 8 * (lane / 32).
+  // KS: two transpose reads; within each 16-lane group lane j addresses row k + j/4, columns 4*(j%4)..+3,
+  //     and receives 4 consecutive k for column (j) of the group's 16 columns.
+  int a_frag, b_frag;
+  if constexpr (AKC) a_frag = (wm * WM + (lane & 31)) * LDA_S + 8 * (lane >> 5);
+  else a_frag = (8 * (lane >> 5) + ((lane & 15) >> 2)) * LDA_S + wm * WM + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  if constexpr (BKC) b_frag = (wn * WN + (lane & 31)) * LDB_S + 8 * (lane >> 5);
+  else b_frag = (8 * (lane >> 5) + ((lane & 15) >> 2)) * LDB_S + wn * WN + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  auto read_a = [&](const bf16_t* s, int ks, int t) -> bf16x8 {
+    if constexpr (AKC) {
+      return *reinterpret_cast<const bf16x8*>(s + a_frag + t * 32 * LDA_S + ks * 16);
+    } else {
+      const bf16_t* q = s + a_frag + ks * 16 * LDA_S + t * 32;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, q));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, q + 4 * LDA_S));
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8, v);
+    }
+  };
+  auto read_b = [&](const bf16_t* s, int ks, int t) -> bf16x8 {
+    if constexpr (BKC) {
+      return *reinterpret_cast<const bf16x8*>(s + b_frag + t * 32 * LDB_S + ks * 16);
+    } else {
+      const bf16_t* q = s + b_frag + ks * 16 * LDB_S + t * 32;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, q));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, q + 4 * LDB_S));
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8, v);
+    }
+  };
+
+  // ---- main loop: global loads of tile t+1 are in flight while tile t is multiplied out of LDS
+  if (k_lo < k_hi) {
+    load_tile(k_lo);
+    store_tile(0);
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = k_lo; k0 < k_hi; k0 += BK) {
+      const bool more = k0 + BK < k_hi;
+      if (more) load_tile(k0 + BK);
+      const bf16_t* a_s = sA[buf];
+      const bf16_t* b_s = sB[buf];
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ks++) {
+        bf16x8 af[TM], bfr[TN];
+#pragma unroll
+        for (int i = 0; i < TM; i++) af[i] = read_a(a_s, ks, i);
+#pragma unroll
+        for (int j = 0; j < TN; j++) bfr[j] = read_b(b_s, ks, j);
+#pragma unroll
+        for (int i = 0; i < TM; i++)
+#pragma unroll
+          for (int j = 0; j < TN; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      }
+      if (more) store_tile(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
+    }
+  }
+
+  // ---- epilogue.  Accumulator element e of a 32x32 tile: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+  OutT* C = reinterpret_cast<OutT*>(p.C) + zo * p.sCo + zi * p.sCi;
+  const bf16_t* R = reinterpret_cast<const bf16_t*>(p.R);
+  if (R) R += zo * p.sCo + zi * p.sCi;
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int col = n0 + wn * WN + j * 32 + (lane & 31);
+      if (col >= p.N) continue;
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        const int row = m0 + wm * WM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        if (row >= p.M) continue;
+        const long idx = (long)row * p.ldc + col;
+        float v = p.alpha * acc[i][j][e];
+        if constexpr (sizeof(OutT) == 4) {
+          if (p.accumulate) v += C[idx];
+          C[idx] = v;
+        } else {
+          if (R) v += (float)R[idx];
+          C[idx] = (OutT)v;
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ fp32
+// 64 x 64 x 16 tile, 256 threads, 4 x 4 outputs per thread; operands addressed through element strides so
+// one kernel serves NN, NT and TN.
+template <typename OutT>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
+  constexpr int TB = 64, TK = 16;
+  __shared__ float As[TK][TB + 4];
+  __shared__ float Bs[TK][TB + 4];
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;
+  const int tm_i = blockIdx.x / p.tiles_n, tn_i = blockIdx.x - tm_i * p.tiles_n;
+  const int m0 = tm_i * TB, n0 = tn_i * TB;
+  int k_lo = 0, k_hi = p.K;
+  if (p.causal == CAUSAL_SKIP_UPPER) {
+    if (n0 > m0 + TB - 1) return;
+  } else if (p.causal == CAUSAL_K_END) {
+    k_hi = (m0 + TB < p.K) ? m0 + TB : p.K;
+  } else if (p.causal == CAUSAL_K_BEGIN) {
+    k_lo = m0;
+  }
+  const int z = blockIdx.z;
+  const int zo = z / p.batch_inner, zi = z - zo * p.batch_inner;
+  const float* A = reinterpret_cast<const float*>(p.A) + zo * p.sAo + zi * p.sAi;
+  const float* B = reinterpret_cast<const float*>(p.B) + zo * p.sBo + zi * p.sBi;
+  float acc[4][4] = {};
+  for (int k0 = k_lo; k0 < k_hi; k0 += TK) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int e = tid + 256 * i;            // 1024 elements of each tile
+      // A tile: consecutive threads along the contiguous direction of the layout
+      int am, ak, bn, bk;
+      if (p.sak == 1) { ak = e & 15; am = e >> 4; } else { am = e & 63; ak = e >> 6; }
+      if (p.sbn == 1) { bn = e & 63; bk = e >> 6; } else { bk = e & 15; bn = e >> 4; }
+      const bool aok = (m0 + am < p.M) && (k0 + ak < k_hi);
+      const bool bok = (n0 + bn < p.N) && (k0 + bk < k_hi);
+      As[ak][am] = aok ? A[(long)(m0 + am) * p.sam + (long)(k0 + ak) * p.sak] : 0.f;
+      Bs[bk][bn] = bok ? B[(long)(k0 + bk) * p.sbk + (long)(n0 + bn) * p.sbn] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < TK; k++) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; i++) a[i] = As[k][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; j++) b[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  OutT* C = reinterpret_cast<OutT*>(p.C) + zo * p.sCo + zi * p.sCi;
+  const float* R = reinterpret_cast<const float*>(p.R);
+  if (R) R += zo * p.sCo + zi * p.sCi;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int row = m0 + ty * 4 + i;
+    if (row >= p.M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const int col = n0 + tx * 4 + j;
+      if (col >= p.N) continue;
+      const long idx = (long)row * p.ldc + col;
+      float v = p.alpha * acc[i][j];
+      if (p.accumulate) v += C[idx];
+      if (R) v += R[idx];
+      C[idx] = v;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ host
+template <int BM, int BN, bool AKC, bool BKC, typename OutT>
+static hipError_t launch_bf16(const GemmParams& p0, int batch, hipStream_t s) {
+  GemmParams p = p0;
+  p.tiles_m = (p.M + BM - 1) / BM;
+  p.tiles_n = (p.N + BN - 1) / BN;
+  constexpr int LDA_S = AKC ? (BK + 8) : (BM + 16);
+  constexpr int LDB_S = BKC ? (BK + 8) : (BN + 16);
+  constexpr int A_ELEMS = AKC ? BM * LDA_S : BK * LDA_S;
+  constexpr int B_ELEMS = BKC ? BN * LDB_S : BK * LDB_S;
+  constexpr size_t smem = 2 * (size_t)(A_ELEMS + B_ELEMS) * sizeof(bf16_t);
+  static_assert(smem <= 160 * 1024, "LDS budget of one gfx950 compute unit");
+  auto kern = gemm_bf16_kernel<BM, BN, AKC, BKC, OutT>;
+  static bool attr_set = false;     // once per instantiation; harmless if two threads race
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)batch);
+  hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
+template <int BM, int BN, typename OutT>
+static hipError_t dispatch_layout(int layout, const GemmParams& p, int batch, hipStream_t s) {
+  switch (layout) {
+    case NN: return launch_bf16<BM, BN, true, false, OutT>(p, batch, s);
+    case NT: return launch_bf16<BM, BN, true, true, OutT>(p, batch, s);
+    case TN: return launch_bf16<BM, BN, false, false, OutT>(p, batch, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
+  if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return hipSuccess;     // empty product: nothing to write
+  GemmParams p{};
+  p.A = g.A; p.B = g.B; p.C = g.C; p.R = g.R;
+  p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
+  p.sAo = g.sAo; p.sAi = g.sAi; p.sBo = g.sBo; p.sBi = g.sBi; p.sCo = g.sCo; p.sCi = g.sCi;
+  p.M = g.M; p.N = g.N; p.K = g.K;
+  p.batch_inner = g.batch_inner > 0 ? g.batch_inner : 1;
+  p.alpha = g.alpha; p.accumulate = g.accumulate; p.causal = g.causal;
+  if (dtype == 0) {
+    switch (g.layout) {
+      case NN: p.sam = g.lda; p.sak = 1; p.sbk = g.ldb; p.sbn = 1; break;
+      case NT: p.sam = g.lda; p.sak = 1; p.sbk = 1; p.sbn = g.ldb; break;
+      case TN: p.sam = 1; p.sak = g.lda; p.sbk = g.ldb; p.sbn = 1; break;
+      default: return hipErrorInvalidValue;
+    }
+    p.tiles_m = (g.M + 63) / 64;
+    p.tiles_n = (g.N + 63) / 64;
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)g.batch);
+    hipLaunchKernelGGL(gemm_f32_kernel<float>, grid, dim3(256), 0, s, p);   // fp32 storage: C is fp32 either way
+    return hipGetLastError();
+  }
+  // bf16: large tiles when the output is big enough to fill 256 compute units with them
+  const long tiles_big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
+  const bool big = g.M >= 256 && g.N >= 256 && tiles_big >= 192;
+  if (g.out_f32) {
+    return big ? dispatch_layout<256, 256, float>(g.layout, p, g.batch, s)
+               : dispatch_layout<128, 128, float>(g.layout, p, g.batch, s);
+  }
+  return big ? dispatch_layout<256, 256, bf16_t>(g.layout, p, g.batch, s)
+             : dispatch_layout<128, 128, bf16_t>(g.layout, p, g.batch, s);
+}
+
+}  // namespace tbp

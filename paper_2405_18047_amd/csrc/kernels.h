@@ -1,0 +1,70 @@
+// Internal launch interface between the stage executor and the gfx950 kernels.
+// Nothing here is part of the public C ABI (see include/tbp.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tbp {
+
+enum Layout { NN = 0, NT = 1, TN = 2 };
+
+// How a product that involves the causal probability matrix restricts its work.  Rows of the
+// probability (and score-gradient) matrices are zero-filled from the diagonal to the next multiple
+// of kCausalPad columns, which is what lets whole K-tiles be skipped safely.
+enum Causal {
+  CAUSAL_NONE = 0,
+  CAUSAL_SKIP_UPPER = 1,  // output [S,S] tiles strictly above the diagonal are not computed (q k^T, do v^T)
+  CAUSAL_K_END = 2,       // A = P or dS [S,S]: contraction stops at the end of the row tile (P v, dS k)
+  CAUSAL_K_BEGIN = 3      // A = P^T or dS^T:   contraction starts at the row tile's first index (P^T do, dS^T q)
+};
+constexpr int kCausalPad = 256;
+
+struct GemmArgs {
+  int layout;            // Layout
+  int M, N, K;
+  float alpha;
+  const void* A; long lda;
+  const void* B; long ldb;
+  void* C; long ldc;
+  const void* R;         // optional residual added before rounding (storage-type output only), same ld as C
+  int out_f32;           // C is fp32
+  int accumulate;        // C += (fp32 output only)
+  int batch;             // grid z; z -> (zo = z / batch_inner, zi = z % batch_inner)
+  int batch_inner;
+  long sAo, sAi, sBo, sBi, sCo, sCi;   // element strides of the outer / inner batch index
+  int causal;            // Causal
+};
+
+inline GemmArgs gemm_args(int layout, int M, int N, int K, const void* A, long lda, const void* B, long ldb,
+                          void* C, long ldc) {
+  GemmArgs g{};
+  g.layout = layout; g.M = M; g.N = N; g.K = K; g.alpha = 1.f;
+  g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
+  g.batch = 1; g.batch_inner = 1;
+  return g;
+}
+
+// dtype: 0 = fp32 storage, 1 = bf16 storage (matches tbp_dtype).
+hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s);
+
+hipError_t rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, const void* g, void* y, hipStream_t s);
+constexpr int kNormPartialBlocks = 256;     // row-block partials of the gain gradient
+hipError_t rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
+                      const void* resid, void* dx, float* dg_out, float* partials, hipStream_t s);
+hipError_t swiglu_fwd(int dtype, int rows, int f, const void* gu, void* m, hipStream_t s);
+hipError_t swiglu_p1(int dtype, int rows, int f, const void* dm, const void* gu, void* dgu, hipStream_t s);
+hipError_t rope_table(int seq, int head_dim, float base, float2* table, hipStream_t s);
+hipError_t rope(int dtype, int rows, int seq, int n_heads, int head_dim, long ld, const float2* table, int inverse,
+                void* x, hipStream_t s);
+hipError_t softmax_fwd(int dtype, long n_rows_total, int seq, int causal, const float* scores, void* P, hipStream_t s);
+hipError_t softmax_p1(int dtype, long n_rows_total, int seq, int causal, const void* P, void* dP, hipStream_t s);
+// out[d] (= or +=) sum over n of parts[n][d] given as n separate pointers packed in a device-free way:
+// parts are rows of one fp32 matrix, selected by index list held in kernel arguments (n <= 64 per launch).
+hipError_t gain_grad_sum(const float* parts, const int* rows_host, int n, int d, int accumulate, float* out,
+                         hipStream_t s);
+
+// Limits enforced by the host before any launch.
+inline int max_d_model(int dtype) { return dtype == 1 ? 8192 : 4096; }
+constexpr int kMaxSeq = 4096;
+
+}  // namespace tbp

@@ -1,0 +1,64 @@
+"""Helpers shared by the GPU parity tests: upload seeded inputs, run the oracle, compare."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2405_18047_amd as tbp
+import seeded_inputs as si
+
+DEV = "cuda:0"
+
+
+def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
+    """float32 array that is exactly representable in `dtype` -> device tensor of that storage type."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    return t.to(DEV, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32).contiguous()
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu", dtype=torch.float64).numpy()
+
+
+def max_rel(got, ref) -> float:
+    """max |got - ref| / max |ref|   (the max-norm relative error used for every tolerance here)."""
+    ref = np.asarray(ref, np.float64)
+    got = np.asarray(got, np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    assert np.all(np.isfinite(got)), "non-finite values in the GPU result"
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-300))
+
+
+def stage_tolerance(dtype: str) -> float:
+    # stated tolerance of the benchmark definition: 1e-4 in fp32 mode, 2e-2 for bf16 against fp64
+    return 2e-2 if dtype == "bf16" else 1e-4
+
+
+def make_gpu_stage(shape: si.StageShape, params: dict, **kw):
+    dev_params = {k: [to_dev(w, shape.dtype) for w in v] for k, v in params.items() if v}
+    return tbp.Stage(tbp.config_from_shape(shape, **kw), dev_params, DEV)
+
+
+def run_oracle(shape, params, xs, dys, concat=False):
+    st = oracle.OracleStage(shape, params)
+    outs = [st.forward(m, xs[m]) for m in range(len(xs))]
+    dxs = [st.backward_p1(m, dys[m]) for m in range(len(xs))]
+    st.backward_p2(range(len(xs)), concat=concat)
+    return outs, dxs, st.grads()
+
+
+def compare_stage(shape, gpu_outs, gpu_dxs, gpu_grads, outs, dxs, grads, tol, label=""):
+    worst = {}
+    for m in range(len(outs)):
+        worst[f"x_out[{m}]"] = max_rel(to_np(gpu_outs[m]), outs[m])
+        worst[f"dx[{m}]"] = max_rel(to_np(gpu_dxs[m]), dxs[m])
+    for k, lst in gpu_grads.items():
+        for l, g in enumerate(lst):
+            worst[f"d{k}[{l}]"] = max_rel(to_np(g), grads[k][l])
+    bad = {k: v for k, v in worst.items() if not v <= tol}
+    print(f"[parity {label}] worst={max(worst.values()):.3e} tol={tol:g} over {len(worst)} tensors", flush=True)
+    assert not bad, bad
+    return worst

@@ -1,0 +1,273 @@
+"""GPU parity: every HIP kernel and the whole stage against the CPU oracle on the same seeded inputs.
+
+Bar: max-norm relative error <= 1e-4 (fp32 storage) and <= 2e-2 (bf16 storage against the fp64 oracle)
+for stage outputs; single kernels are held to tighter bounds derived from their arithmetic (one bf16
+rounding of the output = 2^-9 relative per element; fp32 accumulation otherwise)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import ops
+import paper_2405_18047_amd as tbp
+import seeded_inputs as si
+from gpu_util import DEV, compare_stage, make_gpu_stage, max_rel, run_oracle, stage_tolerance, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _rnd(seed, name, shape, dtype, scale=1.0):
+    return si.store_round(scale * si.standard_normal(seed, name, shape), dtype)
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------------------- GEMM
+GEMM_SHAPES = [  # (M, N, K): several tiles plus ragged tails in every dimension (multiples of 8 for bf16)
+    (256, 256, 64), (520, 392, 200), (1000, 136, 72), (136, 1000, 328), (264, 520, 1096), (8, 8, 8),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("layout", [tbp.NN, tbp.NT, tbp.TN])
+@pytest.mark.parametrize("mnk", GEMM_SHAPES)
+def test_gemm_matches_definition(dtype, layout, mnk):
+    M, N, K = mnk
+    _say(f"gemm dtype={dtype} layout={layout} M,N,K={mnk}")
+    a_shape = (K, M) if layout == tbp.TN else (M, K)
+    b_shape = (N, K) if layout == tbp.NT else (K, N)
+    A, B = _rnd(11, "A", a_shape, dtype), _rnd(11, "B", b_shape, dtype)
+    a64, b64 = A.astype(np.float64), B.astype(np.float64)
+    ref = (a64.T if layout == tbp.TN else a64) @ (b64.T if layout == tbp.NT else b64)
+    dA, dB = to_dev(A, dtype), to_dev(B, dtype)
+    got32 = tbp.tbp_gemm(layout, dA, dB, out_f32=True)
+    assert max_rel(to_np(got32), ref) < 2e-5
+    # accumulate twice on top of a known start, with alpha
+    C0 = _rnd(11, "C0", (M, N), "f32")
+    acc = to_dev(C0, "f32")
+    tbp.tbp_gemm(layout, dA, dB, C_out=acc, accumulate=True, alpha=0.5)
+    tbp.tbp_gemm(layout, dA, dB, C_out=acc, accumulate=True, alpha=0.5)
+    assert max_rel(to_np(acc), ref + C0) < 2e-5
+    if dtype == "bf16":     # storage-type output with a residual, rounded once
+        R = _rnd(11, "R", (M, N), dtype, 4.0)
+        got = tbp.tbp_gemm(layout, dA, dB, R=to_dev(R, dtype))
+        assert max_rel(to_np(got), ref + R) < 3e-3
+
+
+def test_gemm_strided_views_and_empty():
+    # operands that are column blocks of wider matrices (leading dimension > row length), as the stage uses them
+    dtype = "bf16"
+    big = _rnd(12, "big", (300, 3 * 128), dtype)
+    W = _rnd(12, "w", (128, 200), dtype)
+    d_big, d_w = to_dev(big, dtype), to_dev(W, dtype)
+    view = d_big[:, 128:256]
+    got = tbp.tbp_gemm(tbp.NN, view, d_w, out_f32=True)
+    assert max_rel(to_np(got), big[:, 128:256].astype(np.float64) @ W.astype(np.float64)) < 2e-5
+    got = tbp.tbp_gemm(tbp.TN, view, d_big[:, 256:], out_f32=True)
+    assert max_rel(to_np(got), big[:, 128:256].astype(np.float64).T @ big[:, 256:].astype(np.float64)) < 2e-5
+    # K = 0 gives zeros (or leaves an accumulated C alone); M = 0 is a no-op
+    z = tbp.tbp_gemm(tbp.NN, torch.empty((16, 0), dtype=torch.bfloat16, device=DEV),
+                     torch.empty((0, 24), dtype=torch.bfloat16, device=DEV), out_f32=True)
+    assert torch.count_nonzero(z).item() == 0
+    e = tbp.tbp_gemm(tbp.NN, torch.empty((0, 8), dtype=torch.bfloat16, device=DEV), d_w[:8], out_f32=True)
+    assert e.shape == (0, 200)
+
+
+# ------------------------------------------------------------------------------------------- elementwise
+@pytest.mark.parametrize("dtype,rows,d", [("bf16", 37, 4096), ("bf16", 1030, 5120), ("bf16", 5, 264), ("bf16", 3, 8192),
+                                          ("f32", 37, 256), ("f32", 515, 1028), ("f32", 2, 4096)])
+def test_rmsnorm_fwd_and_p1(dtype, rows, d):
+    _say(f"rmsnorm dtype={dtype} rows={rows} d={d}")
+    eps = 1e-6
+    x, dy, res = (_rnd(13, n, (rows, d), dtype) for n in ("x", "dy", "res"))
+    g = _rnd(13, "g", (d,), dtype, 0.1) + si.store_round(np.ones(d), dtype)
+    g = si.store_round(g, dtype)
+    x64, dy64, g64 = x.astype(np.float64), dy.astype(np.float64), g.astype(np.float64)
+    out_tol = 3e-3 if dtype == "bf16" else 2e-6
+    y = tbp.tbp_rmsnorm_fwd(to_dev(x, dtype), to_dev(g, dtype), eps)
+    assert max_rel(to_np(y), ops.rmsnorm_fwd(x64, g64, eps)) < out_tol
+    dx, dg = tbp.tbp_rmsnorm_p1(to_dev(dy, dtype), to_dev(x, dtype), to_dev(g, dtype), eps, resid=to_dev(res, dtype))
+    assert max_rel(to_np(dx), res.astype(np.float64) + ops.rmsnorm_p1(dy64, x64, g64, eps)) < out_tol
+    assert max_rel(to_np(dg), ops.rmsnorm_p2(dy64, x64, eps)) < 2e-5
+    dx2, _ = tbp.tbp_rmsnorm_p1(to_dev(dy, dtype), to_dev(x, dtype), to_dev(g, dtype), eps)
+    assert max_rel(to_np(dx2), ops.rmsnorm_p1(dy64, x64, g64, eps)) < out_tol
+
+
+@pytest.mark.parametrize("dtype,rows,f", [("bf16", 129, 11008), ("bf16", 7, 5504), ("f32", 130, 688), ("f32", 1, 4)])
+def test_swiglu_fwd_and_p1(dtype, rows, f):
+    _say(f"swiglu dtype={dtype} rows={rows} f={f}")
+    gu = _rnd(14, "gu", (rows, 2 * f), dtype, 2.0)
+    dm = _rnd(14, "dm", (rows, f), dtype)
+    gu64, dm64 = gu.astype(np.float64), dm.astype(np.float64)
+    tol = 3e-3 if dtype == "bf16" else 2e-6
+    m = tbp.tbp_swiglu_fwd(to_dev(gu, dtype))
+    assert max_rel(to_np(m), ops.swiglu_fwd(gu64[:, :f], gu64[:, f:])) < tol
+    dgu = tbp.tbp_swiglu_p1(to_dev(dm, dtype), to_dev(gu, dtype))
+    da, db = ops.swiglu_p1(dm64, gu64[:, :f], gu64[:, f:])
+    assert max_rel(to_np(dgu), np.concatenate([da, db], axis=1)) < tol
+
+
+@pytest.mark.parametrize("dtype,seq,nb,H,dh", [("bf16", 1024, 1, 8, 128), ("bf16", 40, 3, 5, 64), ("f32", 128, 2, 4, 64),
+                                               ("f32", 12, 2, 3, 8)])
+def test_rope_fwd_and_inverse(dtype, seq, nb, H, dh):
+    _say(f"rope dtype={dtype} seq={seq} nb={nb} H={H} dh={dh}")
+    rows, ld = seq * nb, H * dh + (dh if dtype == "bf16" else 8)     # a trailing block that must stay untouched
+    x = _rnd(15, "x", (rows, ld), dtype)
+    x64 = x.astype(np.float64)
+    table = tbp.tbp_rope_table(seq, dh, 10000.0)
+    tol = 3e-3 if dtype == "bf16" else 2e-6
+    for inverse in (False, True):
+        got = to_np(tbp.tbp_rope(to_dev(x, dtype), seq, H, dh, table, inverse=inverse))
+        fn = ops.rope_p1 if inverse else ops.rope_fwd
+        assert max_rel(got[:, :H * dh], fn(x64[:, :H * dh], seq, H, dh, 10000.0)) < tol
+        assert np.array_equal(got[:, H * dh:], x64[:, H * dh:])
+
+
+def _softmax_ref(scores, causal):
+    S = scores.shape[-1]
+    s = scores.astype(np.float64)
+    if causal:
+        s = np.where(np.triu(np.ones((S, S), bool), 1), -np.inf, s)
+    e = np.exp(s - s.max(-1, keepdims=True))
+    return e / e.sum(-1, keepdims=True)
+
+
+@pytest.mark.parametrize("dtype,n_mat,seq", [("bf16", 3, 1024), ("bf16", 2, 264), ("bf16", 1, 4096), ("f32", 4, 128),
+                                             ("f32", 2, 260)])
+@pytest.mark.parametrize("causal", [True, False])
+def test_softmax_fwd_and_p1(dtype, n_mat, seq, causal):
+    _say(f"softmax dtype={dtype} n_mat={n_mat} seq={seq} causal={causal}")
+    sc = _rnd(16, "s", (n_mat, seq, seq), "f32", 3.0)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    P = tbp.tbp_softmax_fwd(to_dev(sc, "f32"), causal, tdt)
+    ref = _softmax_ref(sc, causal)
+    got = to_np(P)
+    tol = 3e-3 if dtype == "bf16" else 2e-6
+    assert max_rel(got, ref) < tol
+    if causal:
+        iu = np.triu_indices(seq, 1)
+        assert np.all(got[:, iu[0], iu[1]] == 0)
+    # backward on the stored probabilities (what the stage does): dS = P * (dP - rowsum(dP * P))
+    Pst = si.store_round(ref, dtype)
+    dP = _rnd(16, "dp", (n_mat, seq, seq), dtype)
+    p64, g64 = Pst.astype(np.float64), dP.astype(np.float64)
+    ds_ref = p64 * (g64 - np.sum(g64 * p64, -1, keepdims=True))
+    ddP = to_dev(dP, dtype)
+    if causal:   # the kernel must not depend on what lies above the diagonal: poison it
+        ddP = torch.where(torch.triu(torch.ones(seq, seq, dtype=torch.bool, device=DEV), 1), torch.full_like(ddP, float("nan")), ddP)
+    dS = to_np(tbp.tbp_softmax_p1(to_dev(Pst, dtype), ddP, causal))
+    if causal:   # compare the lower triangle; the zero-filled band must be exact zeros, the rest is never read
+        low = np.tril(np.ones((seq, seq), bool))
+        assert max_rel(np.where(low, dS, 0.0), ds_ref) < tol
+        i, j = np.indices((seq, seq))
+        band = (j > i) & (j < np.minimum(seq, (i // 256 + 1) * 256))
+        assert np.all(dS[:, band] == 0)
+    else:
+        assert max_rel(dS, ds_ref) < tol
+
+
+# ------------------------------------------------------------------------------------------- whole stage
+def _stage_inputs(shape):
+    params = si.stage_params(shape)
+    xs = [si.stage_input(shape, m) for m in range(shape.n_microbatches)]
+    dys = [si.stage_upstream_grad(shape, m) for m in range(shape.n_microbatches)]
+    return params, xs, dys
+
+
+def _run_gpu(shape, params, xs, dys, mode=tbp.TBP_P2_LOOP, accumulate=True, p1_order=None):
+    st = make_gpu_stage(shape, params)
+    n = len(xs)
+    outs = [st.forward(m, to_dev(xs[m], shape.dtype)) for m in range(n)]
+    dxs = [None] * n
+    for m in (p1_order or range(n)):
+        dxs[m] = st.backward_p1(m, to_dev(dys[m], shape.dtype))
+    st.backward_p2(range(n), mode=mode, accumulate=accumulate)
+    torch.cuda.synchronize()
+    return st, outs, dxs
+
+
+SMALL = {
+    "tiny_f32": si.CONFIGS["tiny_f32"],                                   # the benchmark's fp32 configuration, whole
+    "ragged_f32": si.StageShape("ragged_f32", 2, 72, 3, 24, 100, 20, 3, 3, "f32", 31),
+    "small_bf16": si.StageShape("small_bf16", 2, 256, 4, 64, 688, 136, 2, 3, "bf16", 32),
+    "mlp_small_bf16": si.StageShape("mlp_small_bf16", 3, 264, 0, 0, 520, 100, 1, 4, "bf16", 33),
+    "mlp_f32": si.StageShape("mlp_f32", 2, 64, 0, 0, 172, 33, 1, 2, "f32", 34),
+    "tiles_bf16": si.StageShape("tiles_bf16", 1, 512, 4, 128, 1032, 520, 1, 2, "bf16", 35),   # several 256-tiles + tails
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("mode", [tbp.TBP_P2_LOOP, tbp.TBP_P2_KCONCAT])
+def test_stage_matches_oracle(name, mode):
+    shape = SMALL[name]
+    _say(f"stage {name} mode={mode} shape={shape}")
+    params, xs, dys = _stage_inputs(shape)
+    outs, dxs, grads = run_oracle(shape, params, xs, dys)
+    st, g_outs, g_dxs = _run_gpu(shape, params, xs, dys, mode=mode, accumulate=False,
+                                 p1_order=list(reversed(range(len(xs)))))
+    compare_stage(shape, g_outs, g_dxs, st.grads, outs, dxs, grads, stage_tolerance(shape.dtype), f"{name}/{mode}")
+    stats = st.stats()
+    assert stats["w_live_bytes"] == 0 and stats["a_live_bytes"] == 0 and stats["high_water_bytes"] > 0
+    st.close()
+
+
+def test_p2_call_patterns_agree():
+    """p2 right after each p1 (ordinary backprop), p2 by subsets, loop and K-concatenated: same gradients."""
+    shape = SMALL["small_bf16"].replace(n_microbatches=4)
+    params, xs, dys = _stage_inputs(shape)
+    _, _, grads = run_oracle(shape, params, xs, dys)
+    tol = stage_tolerance(shape.dtype)
+    results = []
+    # (a) interleaved: p1(m) then p2({m})
+    st = make_gpu_stage(shape, params, act_slots=1)       # one activation slot is enough for this order
+    for m in range(4):
+        st.forward(m, to_dev(xs[m], shape.dtype))
+        st.backward_p1(m, to_dev(dys[m], shape.dtype))
+        st.backward_p2([m], tbp.TBP_P2_LOOP, accumulate=(m > 0))
+    torch.cuda.synchronize()
+    results.append({k: [to_np(g) for g in v] for k, v in st.grads.items()})
+    st.close()
+    # (b) all forwards, all p1, then p2 on {0,1} K-concatenated (overwrite) and {3,2} looped (accumulate)
+    st = make_gpu_stage(shape, params)
+    for m in range(4):
+        st.forward(m, to_dev(xs[m], shape.dtype))
+    for m in range(4):
+        st.backward_p1(m, to_dev(dys[m], shape.dtype))
+    mid = st.stats()
+    assert mid["a_live_bytes"] == 0 and mid["w_live_bytes"] > 0
+    st.backward_p2([0, 1], tbp.TBP_P2_KCONCAT, accumulate=False)
+    assert st.stats()["w_live_bytes"] * 2 == mid["w_live_bytes"]
+    st.backward_p2([3, 2], tbp.TBP_P2_LOOP, accumulate=True)
+    torch.cuda.synchronize()
+    results.append({k: [to_np(g) for g in v] for k, v in st.grads.items()})
+    # the stage is reusable: micro-batch indices are EMPTY again
+    st.forward(0, to_dev(xs[0], shape.dtype))
+    with pytest.raises(tbp.TbpError):
+        st.backward_p2([0], tbp.TBP_P2_LOOP)
+    with pytest.raises(tbp.TbpError):
+        st.backward_p2([1, 3], tbp.TBP_P2_KCONCAT)
+    st.close()
+    for r in results:
+        for k in r:
+            for l in range(len(r[k])):
+                assert max_rel(r[k][l], grads[k][l]) < tol, (k, l)
+    for k in results[0]:
+        for l in range(len(results[0][k])):
+            assert max_rel(results[0][k][l], results[1][k][l]) < 1e-4     # fp32 summation order only
+
+
+def test_activation_slots_run_out():
+    shape = SMALL["mlp_f32"]
+    params, xs, _ = _stage_inputs(shape)
+    st = make_gpu_stage(shape, params, act_slots=1)
+    st.forward(0, to_dev(xs[0], shape.dtype))
+    with pytest.raises(tbp.TbpError) as e:
+        st.forward(1, to_dev(xs[1], shape.dtype))
+    assert e.value.status == 3
+    with pytest.raises(tbp.TbpError) as e:
+        st.forward(0, to_dev(xs[0], shape.dtype))
+    assert e.value.status == 2
+    torch.cuda.synchronize()
+    st.close()
