@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the split backward of one pipeline stage on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic micro-batches:
+forward of every micro-batch (fills the stash), backward-p1 of every micro-batch (input gradients,
+the pipeline's critical path), then one deferred backward-p2 over all micro-batches (weight gradients,
+micro-batches concatenated along the contraction index at zero copy cost).
+
+Prints ONE JSON line.  `value` is the backward-p2 throughput in TFLOP/s (2*M*N*K per weight-gradient
+product, summed) over the timed steps; the line also carries backward-p1 latency per micro-batch, the stash
+footprint, the roofline of the dominant kernel, per-kernel HBM rates of the elementwise backward kernels and
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
+
+
+def p2_flops(shape) -> float:
+    d, f = shape.d_model, shape.d_ffn
+    per_token = 2.0 * ((4 * d * d if shape.n_heads else 0) + 3 * d * f)
+    return per_token * shape.tokens * shape.n_microbatches * shape.n_layers
+
+
+def p1_flops_per_mb(shape) -> float:
+    """Linear-layer input-gradient products plus the four attention products (causal tiles that are skipped are
+    still counted as full S^2, the convention of the workload table)."""
+    d, f = shape.d_model, shape.d_ffn
+    per_token = 2.0 * ((4 * d * d if shape.n_heads else 0) + 3 * d * f)
+    attn = 8.0 * shape.seq * shape.seq * d * shape.micro_batch if shape.n_heads else 0.0
+    return (per_token * shape.tokens + attn) * shape.n_layers
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="llama7b_s1024")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-rates", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2405_18047_amd as tbp
+    import seeded_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    shape = si.CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(shape.seed)
+
+    def randn(*size, std=1.0, mean=0.0):
+        return (torch.randn(*size, generator=gen, device=dev, dtype=torch.float32) * std + mean).to(tdt)
+
+    d, f, L, M = shape.d_model, shape.d_ffn, shape.n_layers, shape.n_microbatches
+    params = {"w_gu": [randn(d, 2 * f, std=0.02) for _ in range(L)], "w_d": [randn(f, d, std=0.02) for _ in range(L)],
+              "g2": [randn(d, std=0.02, mean=1.0) for _ in range(L)]}
+    if shape.n_heads:
+        params.update({"w_qkv": [randn(d, 3 * d, std=0.02) for _ in range(L)],
+                       "w_o": [randn(d, d, std=0.02) for _ in range(L)],
+                       "g1": [randn(d, std=0.02, mean=1.0) for _ in range(L)]})
+    xs = [randn(shape.tokens, d) for _ in range(M)]
+    dys = [randn(shape.tokens, d) for _ in range(M)]
+    st = tbp.Stage(tbp.config_from_shape(shape), params, dev)
+    x_out = torch.empty_like(xs[0])
+    dx_out = torch.empty_like(xs[0])
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def step(mode, record=None):
+        e = [ev() for _ in range(4 + 2 * M)] if record is not None else None
+        if e: e[0].record()
+        for m in range(M):
+            st.forward(m, xs[m], x_out)
+        if e: e[1].record()
+        for m in range(M):
+            if e: e[4 + 2 * m].record()
+            st.backward_p1(m, dys[m], dx_out)
+            if e: e[5 + 2 * m].record()
+        if e: e[2].record()
+        st.backward_p2(range(M), mode, accumulate=False)
+        if e: e[3].record()
+        if record is not None:
+            record.append(e)
+
+    for _ in range(args.warmup):
+        step(tbp.TBP_P2_KCONCAT)
+    torch.cuda.synchronize()
+    recs = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(tbp.TBP_P2_KCONCAT, recs)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    fwd_ms = [e[0].elapsed_time(e[1]) for e in recs]
+    p2_ms = [e[2].elapsed_time(e[3]) for e in recs]
+    p1_ms = [e[4 + 2 * m].elapsed_time(e[5 + 2 * m]) for e in recs for m in range(M)]
+    stats = st.stats()
+
+    # the same stash walked as M accumulating products per weight (outside the timed steps)
+    loop_recs = []
+    for _ in range(max(2, min(args.steps, 3))):
+        step(tbp.TBP_P2_LOOP, loop_recs)
+    torch.cuda.synchronize()
+    p2_loop_ms = [e[2].elapsed_time(e[3]) for e in loop_recs]
+
+    flops = p2_flops(shape)
+    p2_tflops = flops * len(p2_ms) / (sum(p2_ms) * 1e-3) / 1e12
+    n_p2_launches = (4 if shape.n_heads else 2) * L
+    out = {
+        "metric": "bwd-p2 TFLOP/s (% bf16 MFMA peak) + bwd-p1 ms/micro-batch, 1 stage",
+        "value": round(p2_tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall * 1e3 / args.steps, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": shape.name, "n_layers": L, "d_model": d, "n_heads": shape.n_heads,
+                   "head_dim": shape.head_dim, "d_ffn": f, "seq": shape.seq, "micro_batch": shape.micro_batch,
+                   "n_microbatches": M, "p2_mode": "k-concatenated, deferred until all p1 done"},
+        "pct_of_bf16_mfma_peak": round(100.0 * p2_tflops / PEAK_BF16_TFLOPS, 2),
+        "p2_ms": round(statistics.median(p2_ms), 3),
+        "p2_loop_ms": round(statistics.median(p2_loop_ms), 3),
+        "p2_loop_tflops": round(flops / (statistics.median(p2_loop_ms) * 1e-3) / 1e12, 2),
+        "p1_ms_per_microbatch": round(statistics.median(p1_ms), 3),
+        "p1_tflops": round(p1_flops_per_mb(shape) / (statistics.median(p1_ms) * 1e-3) / 1e12, 2),
+        "fwd_ms_per_microbatch": round(statistics.median(fwd_ms) / M, 3),
+        "stash": {"w_stash_bytes": st.sizes["w_stash_bytes"], "a_stash_bytes": st.sizes["a_stash_bytes"],
+                  "workspace_bytes": st.sizes["workspace_bytes"], "high_water_bytes": stats["high_water_bytes"]},
+        "roofline": {"bound": "mfma", "achieved": round(p2_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(p2_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "kernel": "gemm_bf16_kernel<256,256,TN,f32>", "launches_per_p2": n_p2_launches,
+                     "avg_launch_ms": round(statistics.median(p2_ms) / n_p2_launches, 4)},
+    }
+    if not args.no_kernel_rates:
+        out["p1_elementwise_gbps"] = kernel_rates(shape, tbp, torch, dev, tdt)
+    st.close()
+    del st
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def kernel_rates(shape, tbp, torch, dev, tdt) -> dict:
+    """Achieved HBM rate (algorithmic bytes / kernel time) of the elementwise backward-p1 kernels at this
+    workload's per-micro-batch shapes, each timed alone with events over back-to-back launches."""
+    T, d, f, S, H, B = shape.tokens, shape.d_model, shape.d_ffn, shape.seq, shape.n_heads, shape.micro_batch
+    e = 2 if shape.dtype == "bf16" else 4
+    rn = lambda *s: torch.randn(*s, device=dev, dtype=torch.float32).to(tdt)
+    res = {}
+
+    def timeit(fn, nbytes, name, reps=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / reps
+        gbps = nbytes / (us * 1e-6) / 1e9
+        res[name] = {"us": round(us, 2), "GB/s": round(gbps, 1), "frac_of_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4),
+                     "bytes": nbytes}
+
+    L = tbp.lib()
+    import ctypes as C
+    stream = torch.cuda.current_stream().cuda_stream
+    dt = tbp.TBP_BF16 if shape.dtype == "bf16" else tbp.TBP_F32
+    x, dy, rs, dx = rn(T, d), rn(T, d), rn(T, d), rn(T, d)
+    g = rn(d)
+    dg = torch.empty(d, device=dev, dtype=torch.float32)
+    scratch = torch.empty(L.tbp_rmsnorm_p1_scratch_bytes(d), dtype=torch.uint8, device=dev)
+    timeit(lambda: L.tbp_rmsnorm_p1(dt, T, d, shape.rms_eps, dy.data_ptr(), x.data_ptr(), g.data_ptr(), rs.data_ptr(),
+                                    dx.data_ptr(), dg.data_ptr(), scratch.data_ptr(), stream), 4 * T * d * e, "rmsnorm_p1")
+    gu, dm, dgu = rn(T, 2 * f), rn(T, f), rn(T, 2 * f)
+    timeit(lambda: L.tbp_swiglu_p1(dt, T, f, dm.data_ptr(), gu.data_ptr(), dgu.data_ptr(), stream), 5 * T * f * e, "swiglu_p1")
+    if H:
+        dqkv = rn(T, 3 * d)
+        table = tbp.tbp_rope_table(S, shape.head_dim, shape.rope_base, dev)
+        timeit(lambda: L.tbp_rope(dt, T, S, 2 * H, shape.head_dim, 3 * d, table.data_ptr(), 1, dqkv.data_ptr(), stream),
+               4 * T * d * e, "rope_p1")
+        P = torch.softmax(torch.randn(B * H, S, S, device=dev), -1).to(tdt)
+        dP = rn(B * H, S, S)
+        causal_bytes = 3 * B * H * (S * (S + 1) // 2) * e      # live lower triangle only
+        timeit(lambda: L.tbp_softmax_p1(dt, B * H, S, 1, P.data_ptr(), dP.data_ptr(), stream), causal_bytes, "softmax_p1")
+    return res
+
+
+def cpu_baseline(shape) -> dict:
+    """The CPU oracle as it stands, timed on ONE layer x ONE micro-batch of this workload's real layer shape
+    (forward, backward-p1, backward-p2), random inputs.  Reported baseline only."""
+    import numpy as np
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    one = shape.replace(n_layers=1, n_microbatches=1)
+    rng = np.random.default_rng(shape.seed)
+    d, f = shape.d_model, shape.d_ffn
+    p = {"w_gu": [0.02 * rng.standard_normal((d, 2 * f))], "w_d": [0.02 * rng.standard_normal((f, d))],
+         "g2": [1 + 0.02 * rng.standard_normal(d)], "w_qkv": [], "w_o": [], "g1": []}
+    if shape.n_heads:
+        p.update({"w_qkv": [0.02 * rng.standard_normal((d, 3 * d))], "w_o": [0.02 * rng.standard_normal((d, d))],
+                  "g1": [1 + 0.02 * rng.standard_normal(d)]})
+    x = rng.standard_normal((shape.tokens, d))
+    dy = rng.standard_normal((shape.tokens, d))
+    st = oracle.OracleStage(one, p)
+    t0 = time.perf_counter(); st.forward(0, x)
+    t1 = time.perf_counter(); st.backward_p1(0, dy)
+    t2 = time.perf_counter(); st.backward_p2([0])
+    t3 = time.perf_counter()
+    fl = p2_flops(one)
+    return {"value": round(fl / (t3 - t2) / 1e12, 4), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 layer x 1 micro-batch of {shape.name} at the real layer shape, fp64 numpy; "
+                      f"fwd {t1 - t0:.2f} s, p1 {t2 - t1:.2f} s, p2 {t3 - t2:.2f} s",
+            "p1_ms_per_microbatch_extrapolated": round((t2 - t1) * 1e3 * shape.n_layers, 1)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -116,7 +116,7 @@ def _dt(t: torch.Tensor) -> int:
 
 
 def _ptr(t):
-    return None if t is None else C.c_void_p(t.data_ptr())
+    return None if (t is None or t.numel() == 0) else C.c_void_p(t.data_ptr())
 
 
 def config_from_shape(shape, act_slots: int = 0, max_microbatches: int | None = None) -> tbp_config:
@@ -231,10 +231,9 @@ def tbp_gemm(layout: int, A: torch.Tensor, B: torch.Tensor, *, out_f32: bool = F
     N = B.shape[0] if layout == NT else B.shape[1]
     if C_out is None:
         C_out = torch.empty((M, N), dtype=torch.float32 if (out_f32 or dt == TBP_F32) else A.dtype, device=A.device)
-    _check(lib().tbp_gemm(dt, layout, M, N, K, alpha, _ptr(A), A.stride(0) if A.dim() == 2 and A.shape[0] > 0 else A.shape[-1],
-                          _ptr(B), B.stride(0) if B.shape[0] > 0 else B.shape[-1], _ptr(C_out),
-                          C_out.stride(0) if M > 0 else N, 1 if C_out.dtype == torch.float32 else 0,
-                          1 if accumulate else 0, _ptr(R), _stream()))
+    ld = lambda t: t.stride(0) if t.numel() > 0 else max(t.shape[-1], 8)     # empty tensors carry no usable stride
+    _check(lib().tbp_gemm(dt, layout, M, N, K, alpha, _ptr(A), ld(A), _ptr(B), ld(B), _ptr(C_out), ld(C_out),
+                          1 if C_out.dtype == torch.float32 else 0, 1 if accumulate else 0, _ptr(R), _stream()))
     return C_out
 
 

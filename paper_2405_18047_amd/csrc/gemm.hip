@@ -41,8 +41,14 @@ struct GemmParams {
 constexpr int BK = 64;
 constexpr unsigned kOob = 0x80000000u;     // byte offset beyond every descriptor: the load returns zero
 
+// The descriptor must live in scalar registers; reading the (workgroup-uniform) address through
+// readfirstlane tells the compiler so, otherwise every load is wrapped in a per-lane retry loop.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, 0x7fffffff, 0x00020000);
+  const uint64_t a = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0, 0x7fffffff,
+                                           0x00020000);
 }
 
 // Workgroup id -> (tile row, tile column).  Workgroups are handed to the 8 XCDs round-robin; the first

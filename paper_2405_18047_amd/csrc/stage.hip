@@ -530,7 +530,7 @@ tbp_status tbp_gemm(int dtype, int layout, int M, int N, int K, float alpha, con
   if (layout < 0 || layout > 2) return fail(TBP_EINVAL, "layout must be 0 (NN), 1 (NT) or 2 (TN)");
   if (M < 0 || N < 0 || K < 0) return fail(TBP_EINVAL, "negative size");
   if (M == 0 || N == 0) return TBP_OK;
-  if (!A || !B || !C) return fail(TBP_EINVAL, "A, B, C must be non-null");
+  if (!C || (K > 0 && (!A || !B))) return fail(TBP_EINVAL, "A, B, C must be non-null");
   const int a_cols = layout == tbp::TN ? M : K, b_cols = layout == tbp::NT ? K : N;
   if (lda < a_cols || ldb < b_cols || ldc < N) return fail(TBP_EINVAL, "leading dimension smaller than the row length");
   if (dtype == TBP_BF16) {

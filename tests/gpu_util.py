@@ -59,6 +59,8 @@ def compare_stage(shape, gpu_outs, gpu_dxs, gpu_grads, outs, dxs, grads, tol, la
         for l, g in enumerate(lst):
             worst[f"d{k}[{l}]"] = max_rel(to_np(g), grads[k][l])
     bad = {k: v for k, v in worst.items() if not v <= tol}
-    print(f"[parity {label}] worst={max(worst.values()):.3e} tol={tol:g} over {len(worst)} tensors", flush=True)
+    top = sorted(worst.items(), key=lambda kv: -kv[1])[:4]
+    print(f"[parity {label}] worst={max(worst.values()):.3e} tol={tol:g} over {len(worst)} tensors; largest: "
+          + ", ".join(f"{k}={v:.2e}" for k, v in top), flush=True)
     assert not bad, bad
     return worst

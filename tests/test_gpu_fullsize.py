@@ -1,0 +1,133 @@
+"""Parity at the benchmark's real layer shapes (LLaMa-7B: d_model 4096, 32 heads x 128, FFN 11008, seq 1024).
+
+The full 8-layer x 4-micro-batch oracle costs about 41 TFLOP in fp64, so:
+  * a stage of the real layer shape with fewer layers / micro-batches is compared in full, every tensor;
+  * at the full benchmark configuration, with the launch configuration bench.py times, the forward output of
+    the first tokens of each sequence is compared with the oracle run on the truncated sequence (causal
+    attention: token t depends on tokens <= t only, through every layer), and the weight gradients are checked
+    through properties that hold at any size (loop == K-concatenated, subsets accumulate to the whole).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2405_18047_amd as tbp
+import seeded_inputs as si
+from gpu_util import compare_stage, make_gpu_stage, max_rel, run_oracle, stage_tolerance, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(shape):
+    return (si.stage_params(shape), [si.stage_input(shape, m) for m in range(shape.n_microbatches)],
+            [si.stage_upstream_grad(shape, m) for m in range(shape.n_microbatches)])
+
+
+@pytest.mark.timeout(600)
+def test_real_layer_shape_full_compare():
+    shape = si.CONFIGS["llama7b_s1024"].replace(n_layers=1, n_microbatches=2)
+    print(f"real-shape stage {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    outs, dxs, grads = run_oracle(shape, params, xs, dys)
+    print("oracle done", flush=True)
+    st = make_gpu_stage(shape, params)
+    g_outs = [st.forward(m, to_dev(xs[m], "bf16")) for m in range(2)]
+    g_dxs = [st.backward_p1(m, to_dev(dys[m], "bf16")) for m in range(2)]
+    st.backward_p2([0, 1], tbp.TBP_P2_KCONCAT, accumulate=False)
+    torch.cuda.synchronize()
+    compare_stage(shape, g_outs, g_dxs, st.grads, outs, dxs, grads, stage_tolerance("bf16"), "7B layer shape")
+    st.close()
+
+
+@pytest.mark.timeout(600)
+def test_mlp_config_real_shape_full_compare():
+    shape = si.CONFIGS["mlp_bf16"].replace(n_layers=2, n_microbatches=3)
+    print(f"real-shape MLP stage {shape}", flush=True)
+    params, xs, dys = _inputs(shape)
+    outs, dxs, grads = run_oracle(shape, params, xs, dys)
+    st = make_gpu_stage(shape, params)
+    g_outs = [st.forward(m, to_dev(xs[m], "bf16")) for m in range(3)]
+    g_dxs = [st.backward_p1(m, to_dev(dys[m], "bf16")) for m in range(3)]
+    st.backward_p2([0, 1, 2], tbp.TBP_P2_LOOP, accumulate=False)
+    torch.cuda.synchronize()
+    compare_stage(shape, g_outs, g_dxs, st.grads, outs, dxs, grads, stage_tolerance("bf16"), "MLP real shape")
+    st.close()
+
+
+@pytest.mark.timeout(900)
+def test_full_benchmark_configuration_properties():
+    """Full configuration (8 layers x 4 micro-batches), launch configuration of bench.py: properties that hold at
+    any size.  (End-to-end agreement with fp64 is not asserted at this depth: every stored bf16 intermediate
+    adds about 2^-8 relative noise and the branches dominate the residual at this weight scale, so the error
+    grows with the square root of the depth; per-layer parity at depth is test_deep_stage_per_layer_parity.)"""
+    shape = si.CONFIGS["llama7b_s1024"]
+    print(f"full configuration {shape}", flush=True)
+    params = si.stage_params(shape)
+    print("parameters generated", flush=True)
+    M = shape.n_microbatches
+    xs = [si.stage_input(shape, m) for m in range(M)]
+    dys = [si.stage_upstream_grad(shape, m) for m in range(M)]
+    st = make_gpu_stage(shape, params)
+
+    def run(p2_calls):
+        outs = [st.forward(m, to_dev(xs[m], "bf16")) for m in range(M)]
+        dxs = [st.backward_p1(m, to_dev(dys[m], "bf16")) for m in range(M)]
+        for mbs, mode, acc in p2_calls:
+            st.backward_p2(mbs, mode, accumulate=acc)
+        torch.cuda.synchronize()
+        return outs, dxs, {k: [g.clone() for g in v] for k, v in st.grads.items()}
+
+    outs, dxs, g_cat = run([(range(M), tbp.TBP_P2_KCONCAT, False)])
+    for t in outs + dxs:
+        assert torch.isfinite(t.float()).all()
+    # causality through all 8 layers: the first tokens' outputs equal those of the oracle on the truncated
+    # sequence (loose bound: 8 layers of bf16 storage), and do not depend on later tokens at all on the GPU
+    cut = 48
+    ost = oracle.OracleStage(shape.replace(seq=cut), params)
+    err = max_rel(to_np(outs[0][:cut]), ost.forward(0, xs[0][:cut]))
+    print(f"forward prefix after 8 layers: {err:.3e}", flush=True)
+    assert err < 6e-2
+    # same stash contents, different p2 call patterns
+    _, dxs2, g_loop = run([(range(M), tbp.TBP_P2_LOOP, False)])
+    _, _, g_split = run([([0, 1], tbp.TBP_P2_KCONCAT, False), ([2, 3], tbp.TBP_P2_KCONCAT, True)])
+    for a, b in zip(dxs, dxs2):
+        assert torch.equal(a, b)                      # the path is deterministic
+    for k in g_cat:
+        for l in range(len(g_cat[k])):
+            ref = to_np(g_cat[k][l])
+            assert max_rel(to_np(g_loop[k][l]), ref) < 1e-4, (k, l)
+            assert max_rel(to_np(g_split[k][l]), ref) < 1e-4, (k, l)
+    st.close()
+
+
+@pytest.mark.timeout(900)
+def test_deep_stage_per_layer_parity():
+    """Parity at depth with oracle-supplied layer inputs: the oracle runs one micro-batch through all 8 layers
+    (forward and backward-p1); layers 0, 4 and 7 are then run alone on the GPU from the oracle's layer input and
+    upstream gradient (rounded once to bf16) and compared with the oracle on exactly those rounded inputs."""
+    shape = si.CONFIGS["llama7b_s1024"].replace(n_microbatches=1)
+    params = si.stage_params(shape)
+    x0, dy = si.stage_input(shape, 0), si.stage_upstream_grad(shape, 0)
+    full = oracle.OracleStage(shape, params)
+    layer_in = [np.asarray(x0, np.float64)]
+    for layer in full.layers:
+        layer_in.append(layer.forward(0, layer_in[-1]))
+    print("oracle forward done", flush=True)
+    layer_dy = [None] * shape.n_layers + [np.asarray(dy, np.float64)]
+    for l in reversed(range(shape.n_layers)):
+        layer_dy[l] = full.layers[l].backward_p1(0, layer_dy[l + 1])
+    print("oracle backward-p1 done", flush=True)
+    one = shape.replace(n_layers=1)
+    for l in (0, 4, 7):
+        p_l = {k: [v[l]] for k, v in params.items()}
+        x_l = si.store_round(layer_in[l], "bf16")
+        dy_l = si.store_round(layer_dy[l + 1], "bf16")
+        outs, dxs, grads = run_oracle(one, p_l, [x_l], [dy_l])
+        st = make_gpu_stage(one, p_l)
+        g_out = st.forward(0, to_dev(x_l, "bf16"))
+        g_dx = st.backward_p1(0, to_dev(dy_l, "bf16"))
+        st.backward_p2([0], tbp.TBP_P2_KCONCAT, accumulate=False)
+        torch.cuda.synchronize()
+        compare_stage(one, [g_out], [g_dx], st.grads, outs, dxs, grads, stage_tolerance("bf16"), f"layer {l} of 8")
+        st.close()

@@ -2,7 +2,7 @@
 
 Bar: max-norm relative error <= 1e-4 (fp32 storage) and <= 2e-2 (bf16 storage against the fp64 oracle)
 for stage outputs; single kernels are held to tighter bounds derived from their arithmetic (one bf16
-rounding of the output = 2^-9 relative per element; fp32 accumulation otherwise)."""
+rounding of the output = at most 2^-8 of the element; fp32 accumulation otherwise)."""
 import numpy as np
 import pytest
 import torch
@@ -53,7 +53,7 @@ def test_gemm_matches_definition(dtype, layout, mnk):
     if dtype == "bf16":     # storage-type output with a residual, rounded once
         R = _rnd(11, "R", (M, N), dtype, 4.0)
         got = tbp.tbp_gemm(layout, dA, dB, R=to_dev(R, dtype))
-        assert max_rel(to_np(got), ref + R) < 3e-3
+        assert max_rel(to_np(got), ref + R) < 4.5e-3
 
 
 def test_gemm_strided_views_and_empty():
@@ -85,7 +85,7 @@ def test_rmsnorm_fwd_and_p1(dtype, rows, d):
     g = _rnd(13, "g", (d,), dtype, 0.1) + si.store_round(np.ones(d), dtype)
     g = si.store_round(g, dtype)
     x64, dy64, g64 = x.astype(np.float64), dy.astype(np.float64), g.astype(np.float64)
-    out_tol = 3e-3 if dtype == "bf16" else 2e-6
+    out_tol = 4.5e-3 if dtype == "bf16" else 2e-6
     y = tbp.tbp_rmsnorm_fwd(to_dev(x, dtype), to_dev(g, dtype), eps)
     assert max_rel(to_np(y), ops.rmsnorm_fwd(x64, g64, eps)) < out_tol
     dx, dg = tbp.tbp_rmsnorm_p1(to_dev(dy, dtype), to_dev(x, dtype), to_dev(g, dtype), eps, resid=to_dev(res, dtype))
@@ -101,7 +101,7 @@ def test_swiglu_fwd_and_p1(dtype, rows, f):
     gu = _rnd(14, "gu", (rows, 2 * f), dtype, 2.0)
     dm = _rnd(14, "dm", (rows, f), dtype)
     gu64, dm64 = gu.astype(np.float64), dm.astype(np.float64)
-    tol = 3e-3 if dtype == "bf16" else 2e-6
+    tol = 4.5e-3 if dtype == "bf16" else 2e-6
     m = tbp.tbp_swiglu_fwd(to_dev(gu, dtype))
     assert max_rel(to_np(m), ops.swiglu_fwd(gu64[:, :f], gu64[:, f:])) < tol
     dgu = tbp.tbp_swiglu_p1(to_dev(dm, dtype), to_dev(gu, dtype))
@@ -117,7 +117,7 @@ def test_rope_fwd_and_inverse(dtype, seq, nb, H, dh):
     x = _rnd(15, "x", (rows, ld), dtype)
     x64 = x.astype(np.float64)
     table = tbp.tbp_rope_table(seq, dh, 10000.0)
-    tol = 3e-3 if dtype == "bf16" else 2e-6
+    tol = 4.5e-3 if dtype == "bf16" else 2e-6
     for inverse in (False, True):
         got = to_np(tbp.tbp_rope(to_dev(x, dtype), seq, H, dh, table, inverse=inverse))
         fn = ops.rope_p1 if inverse else ops.rope_fwd
@@ -144,7 +144,7 @@ def test_softmax_fwd_and_p1(dtype, n_mat, seq, causal):
     P = tbp.tbp_softmax_fwd(to_dev(sc, "f32"), causal, tdt)
     ref = _softmax_ref(sc, causal)
     got = to_np(P)
-    tol = 3e-3 if dtype == "bf16" else 2e-6
+    tol = 4.5e-3 if dtype == "bf16" else 2e-6
     assert max_rel(got, ref) < tol
     if causal:
         iu = np.triu_indices(seq, 1)
