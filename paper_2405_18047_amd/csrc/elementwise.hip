@@ -193,19 +193,31 @@ __global__ __launch_bounds__(1024) void rmsnorm_p1_kernel(int rows, int d, float
   }
 }
 
-// out[col] (= or +=) sum_r parts[row_r][col]; rows given by value (host list), fixed summation order.
+// out[col] (= or +=) sum_r parts[row_r][col]; rows given by value (host list) or the first n_first_rows rows.
+// A workgroup covers 32 columns with 8 row lanes each (128-byte coalesced reads, 8 partial sums folded in LDS in
+// a fixed order, so the result is reproducible).
 struct RowList { int n; int idx[64]; };
-__global__ void colsum_kernel(const float* __restrict__ parts, RowList rl, int n_first_rows, int d, int accumulate,
-                              float* __restrict__ out) {
-  const int col = blockIdx.x * blockDim.x + threadIdx.x;
-  if (col >= d) return;
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ parts, RowList rl, int n_first_rows,
+                                                     int d, int accumulate, float* __restrict__ out) {
+  __shared__ float fold[8][33];
+  const int c = threadIdx.x & 31, rlane = threadIdx.x >> 5;
+  const int col = blockIdx.x * 32 + c;
   float s = 0.f;
-  if (n_first_rows > 0) {
-    for (int r = 0; r < n_first_rows; r++) s += parts[(long)r * d + col];
-  } else {
-    for (int r = 0; r < rl.n; r++) s += parts[(long)rl.idx[r] * d + col];
+  if (col < d) {
+    if (n_first_rows > 0) {
+      for (int r = rlane; r < n_first_rows; r += 8) s += parts[(long)r * d + col];
+    } else {
+      for (int r = rlane; r < rl.n; r += 8) s += parts[(long)rl.idx[r] * d + col];
+    }
   }
-  out[col] = accumulate ? out[col] + s : s;
+  fold[rlane][c] = s;
+  __syncthreads();
+  if (rlane == 0 && col < d) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) t += fold[i][c];
+    out[col] = accumulate ? out[col] + t : t;
+  }
 }
 
 // ---- SwiGLU -----------------------------------------------------------------------------------------
@@ -433,7 +445,7 @@ static hipError_t rmsnorm_p1_t(int rows, int d, float eps, const void* dy, const
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   RowList rl{};
-  hipLaunchKernelGGL(colsum_kernel, dim3((d + 255) / 256), dim3(256), 0, s, (const float*)partials, rl, nblk, d, 0,
+  hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, (const float*)partials, rl, nblk, d, 0,
                      dg_out);
   return hipGetLastError();
 }
@@ -441,7 +453,7 @@ hipError_t rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, con
                       const void* resid, void* dx, float* dg_out, float* partials, hipStream_t s) {
   if (rows <= 0) {      // no rows: the gain gradient is zero (written by the same column-sum kernel)
     RowList none{};
-    hipLaunchKernelGGL(colsum_kernel, dim3((d + 255) / 256), dim3(256), 0, s, (const float*)partials, none, 0, d, 0,
+    hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, (const float*)partials, none, 0, d, 0,
                        dg_out);
     return hipGetLastError();
   }
@@ -456,7 +468,7 @@ hipError_t gain_grad_sum(const float* parts, const int* rows_host, int n, int d,
     RowList rl{};
     rl.n = (n - done) < 64 ? (n - done) : 64;
     for (int i = 0; i < rl.n; i++) rl.idx[i] = rows_host[done + i];
-    hipLaunchKernelGGL(colsum_kernel, dim3((d + 255) / 256), dim3(256), 0, s, parts, rl, 0, d,
+    hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, parts, rl, 0, d,
                        (accumulate || done > 0) ? 1 : 0, out);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -12,6 +12,8 @@
 // fp32 path: plain FMA tile kernel with generic strides (the fp32 configuration is tiny).
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace tbp {
 
 typedef __bf16 bf16_t;
@@ -80,10 +82,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   constexpr int B_ELEMS = BKC ? BN * LDB_S : BK * LDB_S;
   constexpr int NA = BM / 32, NB = BN / 32;     // 16-byte global loads per thread per K tile
 
+  // LDS is addressed through 32-bit byte offsets in the LDS address space (no generic-pointer arithmetic)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
-  bf16_t* sA[2] = {smem, smem + A_ELEMS + B_ELEMS};
-  bf16_t* sB[2] = {smem + A_ELEMS, smem + 2 * A_ELEMS + B_ELEMS};
+  typedef __attribute__((address_space(3))) unsigned char lds_u8;
+  lds_u8* const lds = LDS_PTR(unsigned char, smem_raw);
+  constexpr int A_BYTES = A_ELEMS * 2, B_BYTES = B_ELEMS * 2, STAGE_BYTES = A_BYTES + B_BYTES;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -118,7 +121,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     for (int i = 0; i < NA; i++) {
       const int row = (tid >> 3) + 32 * i;
       a_goff[i] = (m0 + row < p.M) ? (unsigned)((long)row * p.lda * 2 + gc * 16) : kOob;
-      a_soff[i] = row * LDA_S + gc * 8;
+      a_soff[i] = (row * LDA_S + gc * 8) * 2;
       a_kidx[i] = gc * 8;
     }
   } else {                        // tile [64 k][BM cols]: BM/8 granules per row
@@ -128,7 +131,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     for (int i = 0; i < NA; i++) {
       const int kr = tid / GPR + RSTEP * i;
       a_goff[i] = (m0 + gc * 8 < p.M) ? (unsigned)((long)kr * p.lda * 2 + gc * 16) : kOob;
-      a_soff[i] = kr * LDA_S + gc * 8;
+      a_soff[i] = (kr * LDA_S + gc * 8) * 2;
       a_kidx[i] = kr;
     }
   }
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     for (int i = 0; i < NB; i++) {
       const int row = (tid >> 3) + 32 * i;
       b_goff[i] = (n0 + row < p.N) ? (unsigned)((long)row * p.ldb * 2 + gc * 16) : kOob;
-      b_soff[i] = row * LDB_S + gc * 8;
+      b_soff[i] = A_BYTES + (row * LDB_S + gc * 8) * 2;
       b_kidx[i] = gc * 8;
     }
   } else {
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     for (int i = 0; i < NB; i++) {
       const int kr = tid / GPR + RSTEP * i;
       b_goff[i] = (n0 + gc * 8 < p.N) ? (unsigned)((long)kr * p.ldb * 2 + gc * 16) : kOob;
-      b_soff[i] = kr * LDB_S + gc * 8;
+      b_soff[i] = A_BYTES + (kr * LDB_S + gc * 8) * 2;
       b_kidx[i] = kr;
     }
   }
@@ -159,25 +162,38 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   const long b_kstep = BKC ? 1 : p.ldb;
 
   u32x4 ra[NA], rb[NB];
-  auto load_tile = [&](int k0) {
-    const int krem = k_hi - k0;             // valid k in this tile: [0, krem)
+  // full K tiles need no per-load range test; only a ragged last tile (TAIL) masks rows / granules beyond k_hi
+  auto load_tile = [&](int k0, auto tail) {
     __amdgpu_buffer_rsrc_t rsA = make_rsrc(Ablk + (long)k0 * a_kstep);
     __amdgpu_buffer_rsrc_t rsB = make_rsrc(Bblk + (long)k0 * b_kstep);
+    if constexpr (decltype(tail)::value) {
+      const int krem = k_hi - k0;           // valid k in this tile: [0, krem)
 #pragma unroll
-    for (int i = 0; i < NA; i++)
-      ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, a_kidx[i] < krem ? a_goff[i] : kOob, 0, 0);
+      for (int i = 0; i < NA; i++)
+        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, a_kidx[i] < krem ? a_goff[i] : kOob, 0, 0);
 #pragma unroll
-    for (int i = 0; i < NB; i++)
-      rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsB, b_kidx[i] < krem ? b_goff[i] : kOob, 0, 0);
+      for (int i = 0; i < NB; i++)
+        rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsB, b_kidx[i] < krem ? b_goff[i] : kOob, 0, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NA; i++) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, a_goff[i], 0, 0);
+#pragma unroll
+      for (int i = 0; i < NB; i++) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsB, b_goff[i], 0, 0);
+    }
+  };
+  auto load_any = [&](int k0) {
+    if (k0 + BK <= k_hi) load_tile(k0, std::false_type{});
+    else load_tile(k0, std::true_type{});
   };
   auto store_tile = [&](int buf) {
+    lds_u8* base = lds + buf * STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < NA; i++) *reinterpret_cast<u32x4*>(sA[buf] + a_soff[i]) = ra[i];
+    for (int i = 0; i < NA; i++) *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(base + a_soff[i]) = ra[i];
 #pragma unroll
-    for (int i = 0; i < NB; i++) *reinterpret_cast<u32x4*>(sB[buf] + b_soff[i]) = rb[i];
+    for (int i = 0; i < NB; i++) *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(base + b_soff[i]) = rb[i];
   };
 
-  // ---- per-lane LDS read offsets of the MFMA operand fragments (elements, k-step 0, tile 0)
+  // ---- per-lane LDS byte offsets of the MFMA operand fragments (k-step 0, MFMA tile 0)
   // KC: row = lane % 32, 8 consecutive k starting at 8 * (lane / 32).
   // KS: two transpose reads; within each 16-lane group lane j addresses row k + j/4, columns 4*(j%4)..+3,
   //     and receives 4 consecutive k for column (j) of the group's 16 columns.
@@ -186,6 +202,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   else a_frag = (8 * (lane >> 5) + ((lane & 15) >> 2)) * LDA_S + wm * WM + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   if constexpr (BKC) b_frag = (wn * WN + (lane & 31)) * LDB_S + 8 * (lane >> 5);
   else b_frag = (8 * (lane >> 5) + ((lane & 15) >> 2)) * LDB_S + wn * WN + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  a_frag *= 2;
+  b_frag = b_frag * 2 + A_BYTES;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -195,49 +213,40 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-  auto read_a = [&](const bf16_t* s, int ks, int t) -> bf16x8 {
-    if constexpr (AKC) {
-      return *reinterpret_cast<const bf16x8*>(s + a_frag + t * 32 * LDA_S + ks * 16);
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  auto read_frag = [&](lds_u8* q, auto kc, int ld_s) -> bf16x8 {
+    if constexpr (decltype(kc)::value) {
+      return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(q);
     } else {
-      const bf16_t* q = s + a_frag + ks * 16 * LDA_S + t * 32;
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, q));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, q + 4 * LDA_S));
-      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<__attribute__((address_space(3))) s16x4*>(q));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          reinterpret_cast<__attribute__((address_space(3))) s16x4*>(q + 4 * ld_s * 2));
       s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       return __builtin_bit_cast(bf16x8, v);
     }
   };
-  auto read_b = [&](const bf16_t* s, int ks, int t) -> bf16x8 {
-    if constexpr (BKC) {
-      return *reinterpret_cast<const bf16x8*>(s + b_frag + t * 32 * LDB_S + ks * 16);
-    } else {
-      const bf16_t* q = s + b_frag + ks * 16 * LDB_S + t * 32;
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, q));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, q + 4 * LDB_S));
-      typedef short s16x8 __attribute__((ext_vector_type(8)));
-      s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      return __builtin_bit_cast(bf16x8, v);
-    }
-  };
+  // byte step of one MFMA tile (32 rows) and of one k-step (16 k) inside a stage, per operand kind
+  constexpr int A_TSTEP = AKC ? 32 * LDA_S * 2 : 32 * 2, A_KSTEP = AKC ? 16 * 2 : 16 * LDA_S * 2;
+  constexpr int B_TSTEP = BKC ? 32 * LDB_S * 2 : 32 * 2, B_KSTEP = BKC ? 16 * 2 : 16 * LDB_S * 2;
 
   // ---- main loop: global loads of tile t+1 are in flight while tile t is multiplied out of LDS
   if (k_lo < k_hi) {
-    load_tile(k_lo);
+    load_any(k_lo);
     store_tile(0);
     __syncthreads();
     int buf = 0;
     for (int k0 = k_lo; k0 < k_hi; k0 += BK) {
       const bool more = k0 + BK < k_hi;
-      if (more) load_tile(k0 + BK);
-      const bf16_t* a_s = sA[buf];
-      const bf16_t* b_s = sB[buf];
+      if (more) load_any(k0 + BK);
+      lds_u8* a_s = lds + buf * STAGE_BYTES + a_frag;
+      lds_u8* b_s = lds + buf * STAGE_BYTES + b_frag;
 #pragma unroll
       for (int ks = 0; ks < BK / 16; ks++) {
         bf16x8 af[TM], bfr[TN];
 #pragma unroll
-        for (int i = 0; i < TM; i++) af[i] = read_a(a_s, ks, i);
+        for (int i = 0; i < TM; i++) af[i] = read_frag(a_s + ks * A_KSTEP + i * A_TSTEP, std::integral_constant<bool, AKC>{}, LDA_S);
 #pragma unroll
-        for (int j = 0; j < TN; j++) bfr[j] = read_b(b_s, ks, j);
+        for (int j = 0; j < TN; j++) bfr[j] = read_frag(b_s + ks * B_KSTEP + j * B_TSTEP, std::integral_constant<bool, BKC>{}, LDB_S);
 #pragma unroll
         for (int i = 0; i < TM; i++)
 #pragma unroll
