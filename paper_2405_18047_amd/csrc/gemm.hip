@@ -1,30 +1,30 @@
 // GEMM kernels for gfx950 (MI355X).
 //
 // bf16 path: C = alpha * op(A) op(B) on the 32x32x16 bf16 MFMA instruction, fp32 accumulation.
-//   One workgroup = 4 wavefronts (2 x 2), block tile BM x BN x 64, double-buffered LDS.
+//   One workgroup = 4 wavefronts (2 x 2), block tile BM x BN, contraction consumed in slices of 32 through a
+//   4-slot LDS ring that is filled by asynchronous global -> LDS copies (no staging registers), so three
+//   slices are in flight while one is multiplied.
 //   An operand whose contraction index is contiguous in memory ("KC": A of NN/NT, B of NT) is kept in
 //   LDS as [row][k] and read as 16-byte vectors; an operand whose contraction index is the slow,
 //   strided one ("KS": A of TN, B of NN/TN, i.e. both operands of dW = X^T dY) is kept as [k][row]
 //   exactly as it sits in memory and transposed on the way to the registers by the LDS
 //   transpose-read instruction (ds_read_b64_tr_b16), so no operand is ever transposed in HBM.
-//   Global loads are buffer loads whose out-of-range lanes are redirected past the end of the
-//   descriptor (they return zero), which handles ragged M, N and K without branches.
+//   Out-of-range lanes of a copy are redirected past the end of the buffer descriptor (they deliver zero),
+//   which handles ragged M, N and K without branches.
 // fp32 path: plain FMA tile kernel with generic strides (the fp32 configuration is tiny).
 #include "kernels.h"
-
-#include <type_traits>
 
 namespace tbp {
 
 typedef __bf16 bf16_t;
 typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
-typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+#define LDS_AS __attribute__((address_space(3)))
 
 struct GemmParams {
   const void* A; const void* B; void* C; const void* R;
@@ -40,17 +40,34 @@ struct GemmParams {
   long sam, sak, sbk, sbn;
 };
 
-constexpr int BK = 64;
-constexpr unsigned kOob = 0x80000000u;     // byte offset beyond every descriptor: the load returns zero
+constexpr int BK = 32;                     // contraction depth of one LDS slot
+constexpr int STAGES = 4;                  // LDS ring: one slot being multiplied, three in flight
+constexpr unsigned kOob = 0x80000000u;     // byte offset beyond every descriptor: the copy delivers zero
 
-// The descriptor must live in scalar registers; reading the (workgroup-uniform) address through
-// readfirstlane tells the compiler so, otherwise every load is wrapped in a per-lane retry loop.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
+typedef LDS_AS unsigned char lds_u8;
+
+// Buffer descriptor of a 2 GiB window starting at p, held in scalar registers (readfirstlane makes the
+// workgroup-uniform address provably uniform for the compiler).
+__device__ __forceinline__ u32x4 make_desc(const void* p) {
   const uint64_t a = reinterpret_cast<uint64_t>(p);
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
-  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
-  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0, 0x7fffffff,
-                                           0x00020000);
+  u32x4 d;
+  d[0] = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)a);
+  d[1] = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  d[2] = 0x7fffffffu;
+  d[3] = 0x00020000u;
+  return d;
+}
+
+// Asynchronous global -> LDS copy of 16 bytes per lane: lane i's data lands at lds_base + 16*i (lds_base is
+// wave-uniform and goes through M0).  The copy is tracked by the vector-memory counter only; it is written as
+// inline assembly so that the compiler's wait insertion does not drain the whole ring before every LDS read.
+__device__ __forceinline__ void dma16(uint32_t lds_base, u32x4 desc, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_base), "v"(voff), "s"(desc) : "memory");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmem() {   // at most N vector-memory operations outstanding
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
 }
 
 // Workgroup id -> (tile row, tile column).  Workgroups are handed to the 8 XCDs round-robin; the first
@@ -72,25 +89,88 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
   tn = r / gsz;
 }
 
+// LDS image of one operand tile (R rows/columns of the output x BK of the contraction), laid out so that
+// (a) every 1 KiB piece is what one wave-wide 16-byte-per-lane copy writes (64 consecutive 16-byte granules),
+// (b) the MFMA fragment reads are free of bank conflicts without padding:
+//   KC (contraction index contiguous in memory): image [R][BK], 4 granules per row; granule g of row r sits in
+//       slot g ^ ((r >> 1) & 3).  A fragment read is one ds_read_b128 per lane.
+//   KS (contraction index strided in memory): image [BK][R] as in memory, R/8 granules per row; granule
+//       pairs (32 bytes = 16 columns) are swizzled: pair q of row k sits in pair slot q ^ (k & 3).  A fragment
+//       read is two ds_read_b64_tr_b16 (transpose reads), each covering 4 k x 16 columns per 16-lane group:
+//       within a group lane j addresses row k + j/4, columns 4*(j%4)..+3 and receives 4 consecutive k of column j.
+template <int R, bool KC>
+struct OperandTile {
+  static constexpr int BYTES = R * BK * 2;
+  static constexpr int CHUNKS = BYTES / 1024;       // wave-wide copies per tile
+  static constexpr int PER_WAVE = CHUNKS / 4;
+  static constexpr int GPR = R / 8;                 // granules per image row (KS)
+  static_assert(CHUNKS % 4 == 0, "tile must split evenly over 4 waves");
+
+  // Global byte offset (relative to the tile origin) and contraction index covered by lane p of chunk c.
+  static __device__ __forceinline__ void copy_plan(int c, int p, long ld, int origin, int extent, unsigned& goff,
+                                                   int& kidx) {
+    if constexpr (KC) {
+      const int row = 16 * c + (p >> 2);
+      const int g = (p & 3) ^ ((row >> 1) & 3);
+      goff = (origin + row < extent) ? (unsigned)((long)row * ld * 2 + g * 16) : kOob;
+      kidx = g * 8;
+    } else {
+      const int P = 64 * c + p;
+      const int k = P / GPR, sl = P % GPR;
+      const int g = ((((sl >> 1) ^ (k & 3)) << 1) | (sl & 1));
+      goff = (origin + g * 8 < extent) ? (unsigned)((long)k * ld * 2 + g * 16) : kOob;
+      kidx = k;
+    }
+  }
+  // Per-lane byte offset inside the image of the fragment of MFMA tile 0 (rows/columns w0..w0+31), variant v:
+  // KC: v = k-step (0, 1);  KS: v = parity of the MFMA tile index.
+  static __device__ __forceinline__ int frag_base(int lane, int w0, int v) {
+    if constexpr (KC) {
+      const int row = w0 + (lane & 31);
+      const int g = 2 * v + (lane >> 5);
+      return row * (BK * 2) + ((g ^ ((row >> 1) & 3)) << 4);
+    } else {
+      const int k = 8 * (lane >> 5) + ((lane & 15) >> 2);
+      const int q = w0 / 16 + ((lane >> 4) & 1) + 2 * v;
+      return k * (R * 2) + ((q ^ (k & 3)) << 5) + 8 * (lane & 3);
+    }
+  }
+  static __device__ __forceinline__ constexpr int variant(int ks, int t) { return KC ? ks : (t & 1); }
+  // Byte offset of (k-step ks, MFMA tile t) relative to frag_base(..., variant(ks, t)).
+  static __device__ __forceinline__ constexpr int frag_step(int ks, int t) {
+    return KC ? t * 32 * BK * 2 : ks * 16 * R * 2 + (t >> 1) * 128;
+  }
+};
+
+template <int R, bool KC>
+__device__ __forceinline__ bf16x8 read_frag(lds_u8* q) {
+  if constexpr (KC) {
+    return *reinterpret_cast<LDS_AS const bf16x8*>(q);
+  } else {
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s16x4*>(q));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s16x4*>(q + 4 * R * 2));
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+  }
+}
+
 template <int BM, int BN, bool AKC, bool BKC, typename OutT>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   constexpr int WM = BM / 2, WN = BN / 2;       // per-wave tile
   constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wave
-  constexpr int LDA_S = AKC ? (BK + 8) : (BM + 16);   // LDS row stride in elements
-  constexpr int LDB_S = BKC ? (BK + 8) : (BN + 16);
-  constexpr int A_ELEMS = AKC ? BM * LDA_S : BK * LDA_S;
-  constexpr int B_ELEMS = BKC ? BN * LDB_S : BK * LDB_S;
-  constexpr int NA = BM / 32, NB = BN / 32;     // 16-byte global loads per thread per K tile
+  using TA = OperandTile<BM, AKC>;
+  using TB = OperandTile<BN, BKC>;
+  constexpr int STAGE_BYTES = TA::BYTES + TB::BYTES;
+  constexpr int NA = TA::PER_WAVE, NB = TB::PER_WAVE;
+  constexpr int L = NA + NB;                    // asynchronous copies per thread per slot
 
-  // LDS is addressed through 32-bit byte offsets in the LDS address space (no generic-pointer arithmetic)
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  typedef __attribute__((address_space(3))) unsigned char lds_u8;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   lds_u8* const lds = LDS_PTR(unsigned char, smem_raw);
-  constexpr int A_BYTES = A_ELEMS * 2, B_BYTES = B_ELEMS * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
   int tm_i, tn_i;
@@ -105,105 +185,50 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   } else if (p.causal == CAUSAL_K_BEGIN) {
     k_lo = m0;
   }
+  const int nk = (k_hi - k_lo + BK - 1) / BK;
 
   const int z = blockIdx.z;
   const int zo = z / p.batch_inner, zi = z - zo * p.batch_inner;
   const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A) + zo * p.sAo + zi * p.sAi;
   const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B) + zo * p.sBo + zi * p.sBi;
 
-  // ---- per-thread global -> LDS copy plan (byte offsets relative to the K-tile origin of each operand)
+  // ---- this wave's share of the global -> LDS copies of one slot: chunks wave, wave + 4, ...
   unsigned a_goff[NA], b_goff[NB];
-  int a_soff[NA], b_soff[NB];
-  int a_kidx[NA], b_kidx[NB];     // k index inside the tile that the load covers (first element)
-  if constexpr (AKC) {            // tile [BM rows][64 k]: 8 granules per row
-    const int gc = tid & 7;
+  int a_kidx[NA], b_kidx[NB];
 #pragma unroll
-    for (int i = 0; i < NA; i++) {
-      const int row = (tid >> 3) + 32 * i;
-      a_goff[i] = (m0 + row < p.M) ? (unsigned)((long)row * p.lda * 2 + gc * 16) : kOob;
-      a_soff[i] = (row * LDA_S + gc * 8) * 2;
-      a_kidx[i] = gc * 8;
-    }
-  } else {                        // tile [64 k][BM cols]: BM/8 granules per row
-    constexpr int GPR = BM / 8, RSTEP = 256 / GPR;
-    const int gc = tid % GPR;
+  for (int i = 0; i < NA; i++) TA::copy_plan(wave + 4 * i, lane, p.lda, m0, p.M, a_goff[i], a_kidx[i]);
 #pragma unroll
-    for (int i = 0; i < NA; i++) {
-      const int kr = tid / GPR + RSTEP * i;
-      a_goff[i] = (m0 + gc * 8 < p.M) ? (unsigned)((long)kr * p.lda * 2 + gc * 16) : kOob;
-      a_soff[i] = (kr * LDA_S + gc * 8) * 2;
-      a_kidx[i] = kr;
-    }
-  }
-  if constexpr (BKC) {
-    const int gc = tid & 7;
-#pragma unroll
-    for (int i = 0; i < NB; i++) {
-      const int row = (tid >> 3) + 32 * i;
-      b_goff[i] = (n0 + row < p.N) ? (unsigned)((long)row * p.ldb * 2 + gc * 16) : kOob;
-      b_soff[i] = A_BYTES + (row * LDB_S + gc * 8) * 2;
-      b_kidx[i] = gc * 8;
-    }
-  } else {
-    constexpr int GPR = BN / 8, RSTEP = 256 / GPR;
-    const int gc = tid % GPR;
-#pragma unroll
-    for (int i = 0; i < NB; i++) {
-      const int kr = tid / GPR + RSTEP * i;
-      b_goff[i] = (n0 + gc * 8 < p.N) ? (unsigned)((long)kr * p.ldb * 2 + gc * 16) : kOob;
-      b_soff[i] = A_BYTES + (kr * LDB_S + gc * 8) * 2;
-      b_kidx[i] = kr;
-    }
-  }
-  // origin of this block's panel at k = 0
-  const bf16_t* Ablk = AKC ? A + (long)m0 * p.lda : A + m0;
+  for (int i = 0; i < NB; i++) TB::copy_plan(wave + 4 * i, lane, p.ldb, n0, p.N, b_goff[i], b_kidx[i]);
+  const bf16_t* Ablk = AKC ? A + (long)m0 * p.lda : A + m0;     // tile origin at k = 0
   const bf16_t* Bblk = BKC ? B + (long)n0 * p.ldb : B + n0;
-  const long a_kstep = AKC ? 1 : p.lda;     // elements per unit of k
+  const long a_kstep = AKC ? 1 : p.lda;                          // elements per unit of k
   const long b_kstep = BKC ? 1 : p.ldb;
 
-  u32x4 ra[NA], rb[NB];
-  // full K tiles need no per-load range test; only a ragged last tile (TAIL) masks rows / granules beyond k_hi
-  auto load_tile = [&](int k0, auto tail) {
-    __amdgpu_buffer_rsrc_t rsA = make_rsrc(Ablk + (long)k0 * a_kstep);
-    __amdgpu_buffer_rsrc_t rsB = make_rsrc(Bblk + (long)k0 * b_kstep);
-    if constexpr (decltype(tail)::value) {
-      const int krem = k_hi - k0;           // valid k in this tile: [0, krem)
-#pragma unroll
-      for (int i = 0; i < NA; i++)
-        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, a_kidx[i] < krem ? a_goff[i] : kOob, 0, 0);
-#pragma unroll
-      for (int i = 0; i < NB; i++)
-        rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsB, b_kidx[i] < krem ? b_goff[i] : kOob, 0, 0);
-    } else {
-#pragma unroll
-      for (int i = 0; i < NA; i++) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, a_goff[i], 0, 0);
-#pragma unroll
-      for (int i = 0; i < NB; i++) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsB, b_goff[i], 0, 0);
-    }
+  // Copies of K tile t into ring slot t % STAGES.  One code path serves full tiles, the ragged last tile and
+  // tiles past the end (t >= nk: every lane is redirected out of range, zeros land in a slot nobody reads
+  // again, no memory traffic), so the main loop needs no branch around it.
+  struct CopyJob { u32x4 dA, dB; uint32_t sa, sb; int krem; };
+  auto make_job = [&](int t) {
+    CopyJob j;
+    const int k0 = k_lo + t * BK;
+    j.dA = make_desc(Ablk + (long)k0 * a_kstep);
+    j.dB = make_desc(Bblk + (long)k0 * b_kstep);
+    j.sa = lds0 + (t % STAGES) * STAGE_BYTES + wave * 1024;
+    j.sb = j.sa + TA::BYTES;
+    j.krem = k_hi - k0;
+    return j;
   };
-  auto load_any = [&](int k0) {
-    if (k0 + BK <= k_hi) load_tile(k0, std::false_type{});
-    else load_tile(k0, std::true_type{});
-  };
-  auto store_tile = [&](int buf) {
-    lds_u8* base = lds + buf * STAGE_BYTES;
-#pragma unroll
-    for (int i = 0; i < NA; i++) *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(base + a_soff[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < NB; i++) *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(base + b_soff[i]) = rb[i];
+  auto copy_one = [&](const CopyJob& j, int c) {     // c-th of this wave's L copies of the job
+    if (c < NA) dma16(j.sa + c * 4096, j.dA, a_kidx[c] < j.krem ? a_goff[c] : kOob);
+    else dma16(j.sb + (c - NA) * 4096, j.dB, b_kidx[c - NA] < j.krem ? b_goff[c - NA] : kOob);
   };
 
-  // ---- per-lane LDS byte offsets of the MFMA operand fragments (k-step 0, MFMA tile 0)
-  // KC: row = lane % 32, 8 consecutive k starting at 8 * (lane / 32).
-  // KS: two transpose reads; within each 16-lane group lane j addresses row k + j/4, columns 4*(j%4)..+3,
-  //     and receives 4 consecutive k for column (j) of the group's 16 columns.
-  int a_frag, b_frag;
-  if constexpr (AKC) a_frag = (wm * WM + (lane & 31)) * LDA_S + 8 * (lane >> 5);
-  else a_frag = (8 * (lane >> 5) + ((lane & 15) >> 2)) * LDA_S + wm * WM + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  if constexpr (BKC) b_frag = (wn * WN + (lane & 31)) * LDB_S + 8 * (lane >> 5);
-  else b_frag = (8 * (lane >> 5) + ((lane & 15) >> 2)) * LDB_S + wn * WN + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  a_frag *= 2;
-  b_frag = b_frag * 2 + A_BYTES;
+  int a_base[2], b_base[2];
+#pragma unroll
+  for (int v = 0; v < 2; v++) {
+    a_base[v] = TA::frag_base(lane, wm * WM, v);
+    b_base[v] = TB::frag_base(lane, wn * WN, v) + TA::BYTES;
+  }
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -213,76 +238,94 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-  typedef short s16x8 __attribute__((ext_vector_type(8)));
-  auto read_frag = [&](lds_u8* q, auto kc, int ld_s) -> bf16x8 {
-    if constexpr (decltype(kc)::value) {
-      return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(q);
-    } else {
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<__attribute__((address_space(3))) s16x4*>(q));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          reinterpret_cast<__attribute__((address_space(3))) s16x4*>(q + 4 * ld_s * 2));
-      s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      return __builtin_bit_cast(bf16x8, v);
+  // ---- main loop, software-pipelined over the two k-steps of a slot and scheduled by hand:
+  //   while (tile t, k-step 0) is multiplied the fragments of (t, k-step 1) are fetched from LDS; then the wait
+  //   for tile t+1 and the workgroup barrier; while (t, k-step 1) is multiplied the fragments of (t+1, k-step 0)
+  //   are fetched and the asynchronous copies of tile t+STAGES-1 are started.  Reads and copies are spread
+  //   between the MFMAs (an MFMA occupies the matrix pipe for 32 cycles, the other instructions issue in its
+  //   shadow); sched_barrier pins that order.
+  // Ring invariant: while tile t is multiplied, tiles t+1 .. t+STAGES-2 are landed or in flight; slot
+  // (t-1) % STAGES is refilled only after a barrier that every wave passes after its last read of tile t-1.
+  // The loop body has no data-dependent join around LDS reads (a join makes the compiler merge wait states and
+  // stall MFMAs on reads they do not need): the last iteration also fetches "tile nk" fragments, stale but
+  // in-bounds LDS contents that are never used.
+  constexpr int MM = TM * TN, UNITS = TM + TN;
+  auto region = [&](const bf16x8* fa, const bf16x8* fb, bf16x8* na, bf16x8* nb, int nt, int nks, const CopyJob* job) {
+    lds_u8* const st = lds + (nt % STAGES) * STAGE_BYTES;
+#pragma unroll
+    for (int m = 0; m < MM; m++) {
+      const int i = m / TN, j = m % TN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+      for (int u = (m * UNITS) / MM; u < ((m + 1) * UNITS) / MM; u++) {
+        if (u < TM) na[u] = read_frag<BM, AKC>(st + a_base[TA::variant(nks, u)] + TA::frag_step(nks, u));
+        else nb[u - TM] = read_frag<BN, BKC>(st + b_base[TB::variant(nks, u - TM)] + TB::frag_step(nks, u - TM));
+      }
+      if (job) {
+#pragma unroll
+        for (int c = (m * L) / MM; c < ((m + 1) * L) / MM; c++) copy_one(*job, c);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // byte step of one MFMA tile (32 rows) and of one k-step (16 k) inside a stage, per operand kind
-  constexpr int A_TSTEP = AKC ? 32 * LDA_S * 2 : 32 * 2, A_KSTEP = AKC ? 16 * 2 : 16 * LDA_S * 2;
-  constexpr int B_TSTEP = BKC ? 32 * LDB_S * 2 : 32 * 2, B_KSTEP = BKC ? 16 * 2 : 16 * LDB_S * 2;
-
-  // ---- main loop: global loads of tile t+1 are in flight while tile t is multiplied out of LDS
-  if (k_lo < k_hi) {
-    load_any(k_lo);
-    store_tile(0);
-    __syncthreads();
-    int buf = 0;
-    for (int k0 = k_lo; k0 < k_hi; k0 += BK) {
-      const bool more = k0 + BK < k_hi;
-      if (more) load_any(k0 + BK);
-      lds_u8* a_s = lds + buf * STAGE_BYTES + a_frag;
-      lds_u8* b_s = lds + buf * STAGE_BYTES + b_frag;
+  static_assert(BK == 32 && STAGES >= 3, "the pipeline is written for two k-steps per slot");
+  if (nk > 0) {
 #pragma unroll
-      for (int ks = 0; ks < BK / 16; ks++) {
-        bf16x8 af[TM], bfr[TN];
+    for (int t = 0; t < STAGES - 1; t++) {
+      const CopyJob j = make_job(t);
 #pragma unroll
-        for (int i = 0; i < TM; i++) af[i] = read_frag(a_s + ks * A_KSTEP + i * A_TSTEP, std::integral_constant<bool, AKC>{}, LDA_S);
-#pragma unroll
-        for (int j = 0; j < TN; j++) bfr[j] = read_frag(b_s + ks * B_KSTEP + j * B_TSTEP, std::integral_constant<bool, BKC>{}, LDB_S);
-#pragma unroll
-        for (int i = 0; i < TM; i++)
-#pragma unroll
-          for (int j = 0; j < TN; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
-      if (more) store_tile(buf ^ 1);
-      __syncthreads();
-      buf ^= 1;
+      for (int c = 0; c < L; c++) copy_one(j, c);
     }
+    wait_vmem<(STAGES - 2) * L>();          // tile 0 has landed (this wave's share)
+    __syncthreads();
+    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    {
+      lds_u8* const st = lds;
+#pragma unroll
+      for (int i = 0; i < TM; i++) fa0[i] = read_frag<BM, AKC>(st + a_base[TA::variant(0, i)] + TA::frag_step(0, i));
+#pragma unroll
+      for (int j = 0; j < TN; j++) fb0[j] = read_frag<BN, BKC>(st + b_base[TB::variant(0, j)] + TB::frag_step(0, j));
+    }
+    for (int t = 0; t < nk; t++) {
+      region(fa0, fb0, fa1, fb1, t, 1, nullptr);
+      wait_vmem<(STAGES - 3) * L>();        // tile t+1 has landed (this wave's share)
+      __syncthreads();                      // everyone's share of t+1 landed; everyone is done with tile t-1
+      const CopyJob j = make_job(t + STAGES - 1);
+      __builtin_amdgcn_sched_barrier(0);
+      region(fa1, fb1, fa0, fb0, t + 1, 0, &j);
+    }
+    wait_vmem<0>();                         // drain the (empty) copies issued past the end
   }
 
   // ---- epilogue.  Accumulator element e of a 32x32 tile: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
   OutT* C = reinterpret_cast<OutT*>(p.C) + zo * p.sCo + zi * p.sCi;
   const bf16_t* R = reinterpret_cast<const bf16_t*>(p.R);
   if (R) R += zo * p.sCo + zi * p.sCi;
+  const bool full = (m0 + BM <= p.M) && (n0 + BN <= p.N);
 #pragma unroll
   for (int i = 0; i < TM; i++) {
 #pragma unroll
     for (int j = 0; j < TN; j++) {
       const int col = n0 + wn * WN + j * 32 + (lane & 31);
-      if (col >= p.N) continue;
+      const int row0 = m0 + wm * WM + i * 32 + 4 * (lane >> 5);
+      OutT* cp = C + (long)row0 * p.ldc + col;
+      const bf16_t* rp = R ? R + (long)row0 * p.ldc + col : nullptr;
 #pragma unroll
       for (int e = 0; e < 16; e++) {
-        const int row = m0 + wm * WM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (row >= p.M) continue;
-        const long idx = (long)row * p.ldc + col;
-        float v = p.alpha * acc[i][j][e];
-        if constexpr (sizeof(OutT) == 4) {
-          if (p.accumulate) v += C[idx];
-          C[idx] = v;
-        } else {
-          if (R) v += (float)R[idx];
-          C[idx] = (OutT)v;
+        const int dr = 8 * (e >> 2) + (e & 3);
+        if (full || (row0 + dr < p.M && col < p.N)) {
+          const long idx = (long)dr * p.ldc;
+          float v = p.alpha * acc[i][j][e];
+          if constexpr (sizeof(OutT) == 4) {
+            if (p.accumulate) v += cp[idx];
+            cp[idx] = v;
+          } else {
+            if (rp) v += (float)rp[idx];
+            cp[idx] = (OutT)v;
+          }
         }
       }
+      __builtin_amdgcn_sched_barrier(0);    // one 32x32 tile at a time keeps the live register set small
     }
   }
 }
@@ -366,11 +409,7 @@ static hipError_t launch_bf16(const GemmParams& p0, int batch, hipStream_t s) {
   GemmParams p = p0;
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N + BN - 1) / BN;
-  constexpr int LDA_S = AKC ? (BK + 8) : (BM + 16);
-  constexpr int LDB_S = BKC ? (BK + 8) : (BN + 16);
-  constexpr int A_ELEMS = AKC ? BM * LDA_S : BK * LDA_S;
-  constexpr int B_ELEMS = BKC ? BN * LDB_S : BK * LDB_S;
-  constexpr size_t smem = 2 * (size_t)(A_ELEMS + B_ELEMS) * sizeof(bf16_t);
+  constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
   static_assert(smem <= 160 * 1024, "LDS budget of one gfx950 compute unit");
   auto kern = gemm_bf16_kernel<BM, BN, AKC, BKC, OutT>;
   static bool attr_set = false;     // once per instantiation; harmless if two threads race
