@@ -47,7 +47,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="llama7b_s1024")
+    ap.add_argument("--config", default="llama7b_s2048")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-rates", action="store_true")
     args = ap.parse_args()

@@ -93,7 +93,8 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
 // (a) every 1 KiB piece is what one wave-wide 16-byte-per-lane copy writes (64 consecutive 16-byte granules),
 // (b) the MFMA fragment reads are free of bank conflicts without padding:
 //   KC (contraction index contiguous in memory): image [R][BK], 4 granules per row; granule g of row r sits in
-//       slot g ^ ((r >> 1) & 3).  A fragment read is one ds_read_b128 per lane.
+//       slot g ^ ((r >> 2) & 3): the 16 lanes served per clock (256 bytes) then touch 16 different 16-byte bank groups.
+//       A fragment read is one ds_read_b128 per lane.
 //   KS (contraction index strided in memory): image [BK][R] as in memory, R/8 granules per row; granule
 //       pairs (32 bytes = 16 columns) are swizzled: pair q of row k sits in pair slot q ^ (k & 3).  A fragment
 //       read is two ds_read_b64_tr_b16 (transpose reads), each covering 4 k x 16 columns per 16-lane group:
@@ -111,7 +112,7 @@ struct OperandTile {
                                                    int& kidx) {
     if constexpr (KC) {
       const int row = 16 * c + (p >> 2);
-      const int g = (p & 3) ^ ((row >> 1) & 3);
+      const int g = (p & 3) ^ ((row >> 2) & 3);
       goff = (origin + row < extent) ? (unsigned)((long)row * ld * 2 + g * 16) : kOob;
       kidx = g * 8;
     } else {
@@ -128,7 +129,7 @@ struct OperandTile {
     if constexpr (KC) {
       const int row = w0 + (lane & 31);
       const int g = 2 * v + (lane >> 5);
-      return row * (BK * 2) + ((g ^ ((row >> 1) & 3)) << 4);
+      return row * (BK * 2) + ((g ^ ((row >> 2) & 3)) << 4);
     } else {
       const int k = 8 * (lane >> 5) + ((lane & 15) >> 2);
       const int q = w0 / 16 + ((lane >> 4) & 1) + 2 * v;
@@ -204,18 +205,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   const long a_kstep = AKC ? 1 : p.lda;                          // elements per unit of k
   const long b_kstep = BKC ? 1 : p.ldb;
 
-  // Copies of K tile t into ring slot t % STAGES.  One code path serves full tiles, the ragged last tile and
-  // tiles past the end (t >= nk: every lane is redirected out of range, zeros land in a slot nobody reads
+  // Copies of the next K tile into the next ring slot.  One code path serves full tiles, the ragged last tile
+  // and tiles past the end ( every lane is redirected out of range, zeros land in a slot nobody reads
   // again, no memory traffic), so the main loop needs no branch around it.
   struct CopyJob { u32x4 dA, dB; uint32_t sa, sb; int krem; };
-  auto make_job = [&](int t) {
+  // Running state of the copy stream (all wave-uniform): next tile's operand addresses, ring slot and remaining k.
+  uint64_t a_next = reinterpret_cast<uint64_t>(Ablk + (long)k_lo * a_kstep);
+  uint64_t b_next = reinterpret_cast<uint64_t>(Bblk + (long)k_lo * b_kstep);
+  const uint64_t a_adv = (uint64_t)(BK * a_kstep * 2), b_adv = (uint64_t)(BK * b_kstep * 2);
+  int slot_next = 0, krem_next = k_hi - k_lo;
+  auto next_job = [&]() {
     CopyJob j;
-    const int k0 = k_lo + t * BK;
-    j.dA = make_desc(Ablk + (long)k0 * a_kstep);
-    j.dB = make_desc(Bblk + (long)k0 * b_kstep);
-    j.sa = lds0 + (t % STAGES) * STAGE_BYTES + wave * 1024;
+    j.dA = make_desc(reinterpret_cast<const void*>(a_next));
+    j.dB = make_desc(reinterpret_cast<const void*>(b_next));
+    j.sa = lds0 + slot_next * STAGE_BYTES + wave * 1024;
     j.sb = j.sa + TA::BYTES;
-    j.krem = k_hi - k0;
+    j.krem = krem_next;
+    a_next += a_adv; b_next += b_adv;
+    slot_next = (slot_next + 1 == STAGES) ? 0 : slot_next + 1;
+    krem_next -= BK;
     return j;
   };
   auto copy_one = [&](const CopyJob& j, int c) {     // c-th of this wave's L copies of the job
@@ -272,7 +280,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   if (nk > 0) {
 #pragma unroll
     for (int t = 0; t < STAGES - 1; t++) {
-      const CopyJob j = make_job(t);
+      const CopyJob j = next_job();
 #pragma unroll
       for (int c = 0; c < L; c++) copy_one(j, c);
     }
@@ -290,7 +298,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
       region(fa0, fb0, fa1, fb1, t, 1, nullptr);
       wait_vmem<(STAGES - 3) * L>();        // tile t+1 has landed (this wave's share)
       __syncthreads();                      // everyone's share of t+1 landed; everyone is done with tile t-1
-      const CopyJob j = make_job(t + STAGES - 1);
+      const CopyJob j = next_job();         // tile t + STAGES - 1
       __builtin_amdgcn_sched_barrier(0);
       region(fa1, fb1, fa0, fb0, t + 1, 0, &j);
     }
