@@ -14,6 +14,9 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 template <typename T> struct Vec;
 template <> struct Vec<float> {
   static constexpr int N = 4;
+  typedef float4 Raw;
+  static __device__ __forceinline__ Raw load_raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  static __device__ __forceinline__ void unpack(const Raw& r, float* v) { v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w; }
   static __device__ __forceinline__ void load(const float* p, float* v) {
     const float4 r = *reinterpret_cast<const float4*>(p);
     v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
@@ -24,6 +27,15 @@ template <> struct Vec<float> {
 };
 template <> struct Vec<bf16_t> {
   static constexpr int N = 8;
+  typedef u32x4 Raw;
+  static __device__ __forceinline__ Raw load_raw(const bf16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+  static __device__ __forceinline__ void unpack(const Raw& r, float* v) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      v[2 * i] = __uint_as_float(r[i] << 16);
+      v[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+    }
+  }
   static __device__ __forceinline__ void load(const bf16_t* p, float* v) {
     const u32x4 r = *reinterpret_cast<const u32x4*>(p);
 #pragma unroll
@@ -41,15 +53,32 @@ template <> struct Vec<bf16_t> {
   }
 };
 
+// Wavefront (64-lane) reductions on the data-parallel-primitive path: four in-row steps (quad swaps, half-row and
+// row mirrors), then the row totals are chained with row_bcast15 / row_bcast31, which leaves the result in lane 63.
+// No LDS traffic and no cross-lane permute unit involved.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float identity, float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, identity),
+                                                               __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_move<0xB1, 0xF>(0.f, v);     // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E, 0xF>(0.f, v);     // quad_perm [2,3,0,1]
+  v += dpp_move<0x141, 0xF>(0.f, v);    // row_half_mirror
+  v += dpp_move<0x140, 0xF>(0.f, v);    // row_mirror: every lane of a 16-lane row holds the row total
+  v += dpp_move<0x142, 0xA>(0.f, v);    // row_bcast15 into rows 1 and 3
+  v += dpp_move<0x143, 0xC>(0.f, v);    // row_bcast31 into rows 2 and 3: lane 63 holds the wave total
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  const float ninf = -INFINITY;
+  v = fmaxf(v, dpp_move<0xB1, 0xF>(ninf, v));
+  v = fmaxf(v, dpp_move<0x4E, 0xF>(ninf, v));
+  v = fmaxf(v, dpp_move<0x141, 0xF>(ninf, v));
+  v = fmaxf(v, dpp_move<0x140, 0xF>(ninf, v));
+  v = fmaxf(v, dpp_move<0x142, 0xA>(ninf, v));
+  v = fmaxf(v, dpp_move<0x143, 0xC>(ninf, v));
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 // ---- RMSNorm forward: one 256-thread workgroup per row ----------------------------------------------
@@ -90,107 +119,123 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(int rows, int d, float
 }
 
 // ---- RMSNorm backward-p1 (+ residual fan-in, + gain-gradient partials) -------------------------------
-// 1024 threads = 4 row groups of 256 threads; group q of workgroup b walks rows 4*b + q, 4*b + q + 4*grid, ...
-// dx = resid + r*yhat - x * r^3 * mean(yhat * x), yhat = dy * g.   Gain gradient: column sums of dy * x * r,
-// kept in registers over the rows a thread sees, folded over the 4 groups in LDS, written as one partial
-// row per workgroup (summed by colsum_kernel: fixed order, so the result is reproducible).
-template <typename T, int MAXC>
-__global__ __launch_bounds__(1024) void rmsnorm_p1_kernel(int rows, int d, float eps, const T* __restrict__ dy,
-                                                          const T* __restrict__ x, const T* __restrict__ g,
-                                                          const T* __restrict__ resid, T* __restrict__ dx,
-                                                          float* __restrict__ partials) {
-  constexpr int N = Vec<T>::N;
-  extern __shared__ float lds[];            // [2][4 groups][2 sums][4 waves] reduction slots, then [3][d] column partials
-  float* red = lds;
-  float* colbuf = lds + 64;
-  const int grp = threadIdx.x >> 8, t = threadIdx.x & 255, wave_in_grp = t >> 6;
+// dx = resid + r*yhat - x * r^3 * mean(yhat * x), yhat = dy * g;  gain gradient: column sums of dy * x * r.
+// 512 threads = 8 waves = 8/WPR row groups of WPR waves; each group owns one row at a time (a row's x and dy are
+// fetched in one go and kept packed in registers, at most MAXC 16-byte vectors per lane).  The two row sums are
+// wavefront reductions; only when a row is wider than one wave can hold (WPR > 1) do the group's waves meet in
+// LDS, with one barrier per row.  Column partials of the gain gradient stay in registers over the rows a group
+// sees and are folded over the groups through LDS in group order (fixed order: reproducible) into one partial row
+// per workgroup, which colsum_kernel adds up.
+template <typename T, int MAXC, int WPR>
+__global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float eps, const T* __restrict__ dy,
+                                                         const T* __restrict__ x, const T* __restrict__ g,
+                                                         const T* __restrict__ resid, T* __restrict__ dx,
+                                                         float* __restrict__ partials) {
+  constexpr int N = Vec<T>::N, G = 8 / WPR, TPR = 64 * WPR;     // groups per workgroup, threads per row
+  typedef typename Vec<T>::Raw Raw;
+  extern __shared__ float lds[];              // [2][8 waves][2 sums] reduction slots, then [d] column buffer
+  float* const red = lds;
+  float* const colbuf = lds + 32;
+  const int wave = threadIdx.x >> 6, grp = wave / WPR, t = threadIdx.x - grp * TPR;
   const int nchunk = d / N;
-  float gv[MAXC][N], cacc[MAXC][N];
+  float cacc[MAXC][N];
 #pragma unroll
-  for (int c = 0; c < MAXC; c++) {
-    const int ch = t + 256 * c;
+  for (int c = 0; c < MAXC; c++)
 #pragma unroll
-    for (int i = 0; i < N; i++) { cacc[c][i] = 0.f; gv[c][i] = 0.f; }
-    if (ch < nchunk) Vec<T>::load(g + ch * N, gv[c]);
-  }
-  const int stride = 4 * gridDim.x;
+    for (int i = 0; i < N; i++) cacc[c][i] = 0.f;
+  const int stride = G * gridDim.x;
   const int iters = (rows + stride - 1) / stride;
   for (int it = 0; it < iters; it++) {
-    const int row = it * stride + 4 * blockIdx.x + grp;
+    const int row = (it * (int)gridDim.x + (int)blockIdx.x) * G + grp;
     const bool live = row < rows;
-    float xv[MAXC][N], yv[MAXC][N];
+    const long base = (long)row * d;
+    Raw xr[MAXC], yr[MAXC];
+#pragma unroll
+    for (int c = 0; c < MAXC; c++) {
+      const int ch = t + TPR * c;
+      if (live && ch < nchunk) {
+        xr[c] = Vec<T>::load_raw(x + base + ch * N);
+        yr[c] = Vec<T>::load_raw(dy + base + ch * N);
+      }
+    }
+    // the gain vector is a few KiB and is re-read from the caches for every row: hiding the pointer from the
+    // optimiser keeps it from hoisting MAXC more live vectors per lane out of the row loop
+    const T* gp = g;
+    asm volatile("" : "+s"(gp));
     float s_xx = 0.f, s_yx = 0.f;
 #pragma unroll
     for (int c = 0; c < MAXC; c++) {
-      const int ch = t + 256 * c;
+      const int ch = t + TPR * c;
       if (live && ch < nchunk) {
-        Vec<T>::load(x + (long)row * d + ch * N, xv[c]);
-        Vec<T>::load(dy + (long)row * d + ch * N, yv[c]);
+        float xv[N], yv[N], gv[N];
+        Vec<T>::unpack(xr[c], xv);
+        Vec<T>::unpack(yr[c], yv);
+        Vec<T>::load(gp + ch * N, gv);
 #pragma unroll
         for (int i = 0; i < N; i++) {
-          s_xx += xv[c][i] * xv[c][i];
-          s_yx += yv[c][i] * gv[c][i] * xv[c][i];
+          s_xx += xv[i] * xv[i];
+          s_yx += yv[i] * gv[i] * xv[i];
         }
       }
     }
     s_xx = wave_sum(s_xx);
     s_yx = wave_sum(s_yx);
-    // two slot sets used alternately: one barrier per row is enough
-    float* slot = red + (it & 1) * 32 + grp * 8;
-    if ((t & 63) == 0) {
-      slot[wave_in_grp] = s_xx;
-      slot[4 + wave_in_grp] = s_yx;
+    if constexpr (WPR > 1) {                  // two slot sets used alternately: one barrier per row is enough
+      float* const slot = red + (it & 1) * 16;
+      if ((threadIdx.x & 63) == 0) {
+        slot[wave * 2] = s_xx;
+        slot[wave * 2 + 1] = s_yx;
+      }
+      __syncthreads();
+      s_xx = 0.f; s_yx = 0.f;
+#pragma unroll
+      for (int w = 0; w < WPR; w++) {
+        s_xx += slot[(grp * WPR + w) * 2];
+        s_yx += slot[(grp * WPR + w) * 2 + 1];
+      }
     }
-    __syncthreads();
-    const float sxx = slot[0] + slot[1] + slot[2] + slot[3];
-    const float syx = slot[4] + slot[5] + slot[6] + slot[7];
-    const float r = rsqrtf(sxx / (float)d + eps);
-    const float coef = r * r * r * (syx / (float)d);
+    const float r = rsqrtf(s_xx / (float)d + eps);
+    const float coef = r * r * r * (s_yx / (float)d);
 #pragma unroll
     for (int c = 0; c < MAXC; c++) {
-      const int ch = t + 256 * c;
+      const int ch = t + TPR * c;
       if (live && ch < nchunk) {
-        float o[N];
-        if (resid) Vec<T>::load(resid + (long)row * d + ch * N, o);
+        float xv[N], yv[N], gv[N], o[N];
+        Vec<T>::unpack(xr[c], xv);
+        Vec<T>::unpack(yr[c], yv);
+        Vec<T>::load(gp + ch * N, gv);
+        if (resid) Vec<T>::load(resid + base + ch * N, o);
         else {
 #pragma unroll
           for (int i = 0; i < N; i++) o[i] = 0.f;
         }
 #pragma unroll
         for (int i = 0; i < N; i++) {
-          o[i] += r * yv[c][i] * gv[c][i] - xv[c][i] * coef;
-          cacc[c][i] += yv[c][i] * xv[c][i] * r;
+          o[i] += r * yv[i] * gv[i] - xv[i] * coef;
+          cacc[c][i] += yv[i] * xv[i] * r;
         }
-        Vec<T>::store(dx + (long)row * d + ch * N, o);
-      }
-    }
-  }
-  // fold the 4 groups' column partials: groups 1..3 publish, group 0 adds and writes the workgroup's row
-  __syncthreads();
-  if (grp > 0) {
-#pragma unroll
-    for (int c = 0; c < MAXC; c++) {
-      const int ch = t + 256 * c;
-      if (ch < nchunk) {
-#pragma unroll
-        for (int i = 0; i < N; i++) colbuf[(grp - 1) * d + ch * N + i] = cacc[c][i];
+        Vec<T>::store(dx + base + ch * N, o);
       }
     }
   }
   __syncthreads();
-  if (grp == 0) {
+  for (int gi = 0; gi < G; gi++) {
+    if (grp == gi) {
 #pragma unroll
-    for (int c = 0; c < MAXC; c++) {
-      const int ch = t + 256 * c;
-      if (ch < nchunk) {
+      for (int c = 0; c < MAXC; c++) {
+        const int ch = t + TPR * c;
+        if (ch < nchunk) {
 #pragma unroll
-        for (int i = 0; i < N; i++) {
-          const int col = ch * N + i;
-          partials[(long)blockIdx.x * d + col] = cacc[c][i] + colbuf[col] + colbuf[d + col] + colbuf[2 * d + col];
+          for (int i = 0; i < N; i++) {
+            const int col = ch * N + i;
+            colbuf[col] = (gi == 0 ? 0.f : colbuf[col]) + cacc[c][i];
+          }
         }
       }
     }
+    __syncthreads();
   }
+  for (int col = threadIdx.x; col < d; col += 512) partials[(long)blockIdx.x * d + col] = colbuf[col];
 }
 
 // out[col] (= or +=) sum_r parts[row_r][col]; rows given by value (host list) or the first n_first_rows rows.
@@ -419,30 +464,34 @@ hipError_t rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, con
   return dtype ? rmsnorm_fwd_t<bf16_t>(rows, d, eps, x, g, y, s) : rmsnorm_fwd_t<float>(rows, d, eps, x, g, y, s);
 }
 
+template <typename T, int WPR>
+static hipError_t rmsnorm_p1_w(int rows, int d, float eps, const T* dy, const T* x, const T* g, const T* resid, T* dx,
+                               float* partials, int* nblk_out, hipStream_t s) {
+  constexpr int G = 8 / WPR;
+  const int c = (d / Vec<T>::N + 64 * WPR - 1) / (64 * WPR);      // vectors per lane
+  int nblk = (rows + G - 1) / G;
+  if (nblk > kNormPartialBlocks) nblk = kNormPartialBlocks;
+  *nblk_out = nblk;
+  const size_t smem = (32 + (size_t)d) * sizeof(float);
+  const dim3 grid(nblk), block(512);
+  if (c <= 1) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 1, WPR>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
+  else if (c <= 2) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 2, WPR>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
+  else if (c <= 4) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 4, WPR>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
 template <typename T>
 static hipError_t rmsnorm_p1_t(int rows, int d, float eps, const void* dy, const void* x, const void* g,
                                const void* resid, void* dx, float* dg_out, float* partials, hipStream_t s) {
-  const int c = chunks_per_thread(d, Vec<T>::N);
-  int nblk = (rows + 3) / 4;
-  if (nblk > kNormPartialBlocks) nblk = kNormPartialBlocks;
-  const size_t smem = (64 + 3 * (size_t)d) * sizeof(float);
   auto DY = (const T*)dy; auto X = (const T*)x; auto G = (const T*)g; auto RS = (const T*)resid; auto DX = (T*)dx;
-#define TBP_LAUNCH_NP1(C)                                                                                          \
-  do {                                                                                                             \
-    auto kern = rmsnorm_p1_kernel<T, C>;                                                                           \
-    if (smem > 64 * 1024) {                                                                                        \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                      \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                   \
-      if (e != hipSuccess) return e;                                                                               \
-    }                                                                                                              \
-    hipLaunchKernelGGL(kern, dim3(nblk), dim3(1024), smem, s, rows, d, eps, DY, X, G, RS, DX, partials);           \
-  } while (0)
-  if (c <= 1) TBP_LAUNCH_NP1(1);
-  else if (c <= 2) TBP_LAUNCH_NP1(2);
-  else if (c <= 4) TBP_LAUNCH_NP1(4);
-  else return hipErrorInvalidValue;
-#undef TBP_LAUNCH_NP1
-  hipError_t e = hipGetLastError();
+  const int wc = (d / Vec<T>::N + 63) / 64;         // vectors per lane if one wave owned a whole row
+  int nblk = 0;
+  hipError_t e;
+  if (wc <= 4) e = rmsnorm_p1_w<T, 1>(rows, d, eps, DY, X, G, RS, DX, partials, &nblk, s);
+  else if (wc <= 8) e = rmsnorm_p1_w<T, 2>(rows, d, eps, DY, X, G, RS, DX, partials, &nblk, s);
+  else if (wc <= 16) e = rmsnorm_p1_w<T, 4>(rows, d, eps, DY, X, G, RS, DX, partials, &nblk, s);
+  else e = rmsnorm_p1_w<T, 8>(rows, d, eps, DY, X, G, RS, DX, partials, &nblk, s);
   if (e != hipSuccess) return e;
   RowList rl{};
   hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, (const float*)partials, rl, nblk, d, 0,

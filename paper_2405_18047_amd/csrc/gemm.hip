@@ -22,6 +22,7 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 #define LDS_AS __attribute__((address_space(3)))
@@ -175,7 +176,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   const int wm = wave >> 1, wn = wave & 1;
 
   int tm_i, tn_i;
-  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm_i, tn_i);
+  if (gridDim.z == 1) {
+    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm_i, tn_i);
+  } else {
+    // Batched (per-head) products: the causal variants do an amount of work that depends on the tile row, and the
+    // hardware hands consecutive workgroup ids to the 8 XCDs in turn, so a fixed id -> tile map would give one XCD
+    // all the long tiles of every head.  Rotating the map by the batch index spreads them evenly.
+    const int nt = (int)gridDim.x;
+    int id = ((int)blockIdx.x + 3 * (int)blockIdx.z) % nt;
+    if (p.causal == CAUSAL_SKIP_UPPER && p.tiles_m == p.tiles_n) {
+      // only the lower-triangular tiles are launched: id = tm (tm + 1) / 2 + tn
+      tm_i = (int)((__builtin_sqrtf(8.f * (float)id + 1.f) - 1.f) * 0.5f);
+      while (tm_i * (tm_i + 1) / 2 > id) tm_i--;
+      while ((tm_i + 1) * (tm_i + 2) / 2 <= id) tm_i++;
+      tn_i = id - tm_i * (tm_i + 1) / 2;
+    } else {
+      tm_i = id % p.tiles_m;
+      tn_i = id / p.tiles_m;
+    }
+  }
   const int m0 = tm_i * BM, n0 = tn_i * BN;
 
   int k_lo = 0, k_hi = p.K;
@@ -305,35 +324,65 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     wait_vmem<0>();                         // drain the (empty) copies issued past the end
   }
 
-  // ---- epilogue.  Accumulator element e of a 32x32 tile: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+  // ---- epilogue.  Accumulator element e of a 32x32 tile sits at row 8*(e/4) + 4*(lane/32) + e%4, column lane%32:
+  // a lane owns single elements of many rows.  Each wave therefore passes its tile through LDS one 32-row strip at
+  // a time (the ring is free by now) and reads it back row-major, so that every lane stores 16 contiguous bytes
+  // and a wave-wide store covers whole rows of the tile.
+  __syncthreads();                          // every wave is done with the ring
   OutT* C = reinterpret_cast<OutT*>(p.C) + zo * p.sCo + zi * p.sCi;
   const bf16_t* R = reinterpret_cast<const bf16_t*>(p.R);
   if (R) R += zo * p.sCo + zi * p.sCi;
-  const bool full = (m0 + BM <= p.M) && (n0 + BN <= p.N);
+  constexpr int SW = WN + 4;                // strip row stride in floats
+  typedef LDS_AS float lds_f32;
+  lds_f32* const strip = reinterpret_cast<lds_f32*>(lds + wave * (32 * SW * 4));
+  static_assert(4 * 32 * SW * 4 <= STAGES * STAGE_BYTES, "strips must fit in the ring");
+  constexpr int V = sizeof(OutT) == 4 ? 4 : 8;          // elements per 16-byte store
+  constexpr int LPR = WN / V, RPI = 64 / LPR;           // lanes per strip row, rows per wave-wide store
+  const int sr = lane / LPR, sc = (lane % LPR) * V;
+  const int gcol = n0 + wn * WN + sc;
 #pragma unroll
   for (int i = 0; i < TM; i++) {
 #pragma unroll
-    for (int j = 0; j < TN; j++) {
-      const int col = n0 + wn * WN + j * 32 + (lane & 31);
-      const int row0 = m0 + wm * WM + i * 32 + 4 * (lane >> 5);
-      OutT* cp = C + (long)row0 * p.ldc + col;
-      const bf16_t* rp = R ? R + (long)row0 * p.ldc + col : nullptr;
+    for (int j = 0; j < TN; j++)
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        const int dr = 8 * (e >> 2) + (e & 3);
-        if (full || (row0 + dr < p.M && col < p.N)) {
-          const long idx = (long)dr * p.ldc;
-          float v = p.alpha * acc[i][j][e];
-          if constexpr (sizeof(OutT) == 4) {
-            if (p.accumulate) v += cp[idx];
-            cp[idx] = v;
-          } else {
-            if (rp) v += (float)rp[idx];
-            cp[idx] = (OutT)v;
+      for (int e = 0; e < 16; e++)
+        strip[(8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * SW + j * 32 + (lane & 31)] = p.alpha * acc[i][j][e];
+#pragma unroll
+    for (int it = 0; it < 32 / RPI; it++) {
+      const int r = it * RPI + sr;
+      const int grow = m0 + wm * WM + i * 32 + r;
+      if (grow < p.M && gcol < p.N) {       // N is a multiple of 8: a vector is inside or outside as a whole
+        const long idx = (long)grow * p.ldc + gcol;
+        float v[V];
+#pragma unroll
+        for (int q = 0; q < V; q += 4) {
+          const f32x4 t4 = *reinterpret_cast<LDS_AS const f32x4*>(strip + r * SW + sc + q);
+          v[q] = t4[0]; v[q + 1] = t4[1]; v[q + 2] = t4[2]; v[q + 3] = t4[3];
+        }
+        if constexpr (sizeof(OutT) == 4) {
+          f32x4* dst = reinterpret_cast<f32x4*>(C + idx);
+          if (p.accumulate) {
+            const f32x4 o = *dst;
+            v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
           }
+          f32x4 w4;
+          w4[0] = v[0]; w4[1] = v[1]; w4[2] = v[2]; w4[3] = v[3];
+          *dst = w4;
+        } else {
+          if (R) {
+            const u32x4 rr = *reinterpret_cast<const u32x4*>(R + idx);
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+              v[2 * q] += __uint_as_float(rr[q] << 16);
+              v[2 * q + 1] += __uint_as_float(rr[q] & 0xffff0000u);
+            }
+          }
+          bf16x8 o;
+#pragma unroll
+          for (int q = 0; q < 8; q++) o[q] = (bf16_t)v[q];
+          *reinterpret_cast<bf16x8*>(C + idx) = o;
         }
       }
-      __builtin_amdgcn_sched_barrier(0);    // one 32x32 tile at a time keeps the live register set small
     }
   }
 }
@@ -427,7 +476,10 @@ static hipError_t launch_bf16(const GemmParams& p0, int batch, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)batch);
+  unsigned nt = (unsigned)(p.tiles_m * p.tiles_n);
+  if (batch > 1 && p.causal == CAUSAL_SKIP_UPPER && p.tiles_m == p.tiles_n)
+    nt = (unsigned)(p.tiles_m * (p.tiles_m + 1) / 2);       // lower-triangular tiles only
+  dim3 grid(nt, 1, (unsigned)batch);
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, p);
   return hipGetLastError();
 }

@@ -536,7 +536,9 @@ tbp_status tbp_gemm(int dtype, int layout, int M, int N, int K, float alpha, con
   if (dtype == TBP_BF16) {
     if (a_cols % 8 || b_cols % 8 || lda % 8 || ldb % 8)
       return fail(TBP_EINVAL, "bf16 operands need contiguous extents and leading dimensions that are multiples of 8");
-    if ((uintptr_t)A % 16 || (uintptr_t)B % 16) return fail(TBP_EINVAL, "bf16 operands must be 16-byte aligned");
+    if ((uintptr_t)A % 16 || (uintptr_t)B % 16 || (uintptr_t)C % 16 || (R && (uintptr_t)R % 16))
+      return fail(TBP_EINVAL, "bf16-path operands, output and residual must be 16-byte aligned");
+    if (N % 8 || ldc % 8) return fail(TBP_EINVAL, "bf16 path needs N and ldc to be multiples of 8");
   }
   if (dtype == TBP_F32) out_f32 = 1;
   if (accumulate && !out_f32) return fail(TBP_EINVAL, "accumulate needs an fp32 output");
