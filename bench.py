@@ -50,6 +50,11 @@ def main() -> int:
     ap.add_argument("--config", default="llama7b_s2048")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-rates", action="store_true")
+    ap.add_argument("--no-loop-compare", action="store_true",
+                    help="skip the extra loop-mode p2 steps (profiles: every dW launch is then a K-concatenated one)")
+    ap.add_argument("--probe", action="store_true",
+                    help="for hardware-counter runs: one forward/p1 pass, then a plain 1 GiB device copy (calibration) "
+                         "and two K-concatenated p2 passes; prints nothing but a marker line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -104,6 +109,23 @@ def main() -> int:
         if record is not None:
             record.append(e)
 
+    if args.probe:
+        for m in range(M):
+            st.forward(m, xs[m], x_out)
+        for m in range(M):
+            st.backward_p1(m, dys[m], dx_out)
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)                     # plain copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        st.backward_p2(range(M), tbp.TBP_P2_KCONCAT, accumulate=False)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": shape.name, "copy_bytes": 1 << 30, "p2_launches": (4 if shape.n_heads else 2) * L}))
+        st.close()
+        return 0
+
     for _ in range(args.warmup):
         step(tbp.TBP_P2_KCONCAT)
     torch.cuda.synchronize()
@@ -120,10 +142,11 @@ def main() -> int:
 
     # the same stash walked as M accumulating products per weight (outside the timed steps)
     loop_recs = []
-    for _ in range(max(2, min(args.steps, 3))):
-        step(tbp.TBP_P2_LOOP, loop_recs)
-    torch.cuda.synchronize()
-    p2_loop_ms = [e[2].elapsed_time(e[3]) for e in loop_recs]
+    if not args.no_loop_compare:
+        for _ in range(max(2, min(args.steps, 3))):
+            step(tbp.TBP_P2_LOOP, loop_recs)
+        torch.cuda.synchronize()
+    p2_loop_ms = [e[2].elapsed_time(e[3]) for e in loop_recs] or [float("nan")]
 
     flops = p2_flops(shape)
     p2_tflops = flops * len(p2_ms) / (sum(p2_ms) * 1e-3) / 1e12
@@ -138,8 +161,8 @@ def main() -> int:
                    "n_microbatches": M, "p2_mode": "k-concatenated, deferred until all p1 done"},
         "pct_of_bf16_mfma_peak": round(100.0 * p2_tflops / PEAK_BF16_TFLOPS, 2),
         "p2_ms": round(statistics.median(p2_ms), 3),
-        "p2_loop_ms": round(statistics.median(p2_loop_ms), 3),
-        "p2_loop_tflops": round(flops / (statistics.median(p2_loop_ms) * 1e-3) / 1e12, 2),
+        "p2_loop_ms": None if args.no_loop_compare else round(statistics.median(p2_loop_ms), 3),
+        "p2_loop_tflops": None if args.no_loop_compare else round(flops / (statistics.median(p2_loop_ms) * 1e-3) / 1e12, 2),
         "p1_ms_per_microbatch": round(statistics.median(p1_ms), 3),
         "p1_tflops": round(p1_flops_per_mb(shape) / (statistics.median(p1_ms) * 1e-3) / 1e12, 2),
         "fwd_ms_per_microbatch": round(statistics.median(fwd_ms) / M, 3),
@@ -150,6 +173,12 @@ def main() -> int:
                      "kernel": "gemm_bf16_kernel<256,256,TN,f32>", "launches_per_p2": n_p2_launches,
                      "avg_launch_ms": round(statistics.median(p2_ms) / n_p2_launches, 4)},
     }
+    traffic_file = os.path.join(ROOT, "profiles", "p2_traffic.json")
+    if os.path.exists(traffic_file):           # HBM bytes per p2 launch from the committed hardware-counter runs
+        with open(traffic_file) as fh:
+            t = json.load(fh).get(shape.name)
+        if t:
+            out["roofline"]["traffic"] = t["hbm_bytes_per_launch"]
     if not args.no_kernel_rates:
         out["p1_elementwise_gbps"] = kernel_rates(shape, tbp, torch, dev, tdt)
     st.close()
