@@ -517,14 +517,51 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
     return hipGetLastError();
   }
   // bf16: large tiles when the output is big enough to fill 256 compute units with them
-  const long tiles_big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256) * g.batch;
+  const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
+  const long tiles_big = (long)tiles_m * tiles_n * g.batch;
   const bool big = g.M >= 256 && g.N >= 256 && tiles_big >= 192;
-  if (g.out_f32) {
-    return big ? dispatch_layout<256, 256, float>(g.layout, p, g.batch, s)
-               : dispatch_layout<128, 128, float>(g.layout, p, g.batch, s);
+  auto run = [&](const GemmParams& q, bool use_big) -> hipError_t {
+    if (g.out_f32)
+      return use_big ? dispatch_layout<256, 256, float>(g.layout, q, g.batch, s)
+                     : dispatch_layout<128, 128, float>(g.layout, q, g.batch, s);
+    return use_big ? dispatch_layout<256, 256, bf16_t>(g.layout, q, g.batch, s)
+                   : dispatch_layout<128, 128, bf16_t>(g.layout, q, g.batch, s);
+  };
+  // Tail quantisation: with nt large tiles on 256 compute units the last round runs nt % 256 workgroups.  When
+  // that round would be less than half full, the output is cut along its longer side into a part made of whole
+  // rounds of large tiles and a remainder that is run with 128 x 128 tiles (four times as many workgroups).
+  const long rem = tiles_big % 256;
+  if (big && g.batch == 1 && g.causal == CAUSAL_NONE && tiles_big > 256 && rem != 0 && rem <= 128) {
+    const long whole = tiles_big - rem;
+    const size_t ce = g.out_f32 ? 4 : 2;
+    GemmParams a = p, b = p;
+    if (tiles_n >= tiles_m) {                       // cut along N
+      const int cols = (int)(whole / tiles_m);      // tile columns of the first part
+      if (cols > 0 && cols < tiles_n) {
+        const long n0 = (long)cols * 256;
+        a.N = (int)n0;
+        b.N = g.N - (int)n0;
+        b.B = (const char*)p.B + (g.layout == NT ? n0 * g.ldb : n0) * 2;
+        b.C = (char*)p.C + n0 * ce;
+        if (p.R) b.R = (const char*)p.R + n0 * 2;
+        hipError_t e = run(a, true);
+        return e != hipSuccess ? e : run(b, false);
+      }
+    } else {                                        // cut along M
+      const int rows = (int)(whole / tiles_n);
+      if (rows > 0 && rows < tiles_m) {
+        const long m0 = (long)rows * 256;
+        a.M = (int)m0;
+        b.M = g.M - (int)m0;
+        b.A = (const char*)p.A + (g.layout == TN ? m0 : m0 * g.lda) * 2;
+        b.C = (char*)p.C + m0 * g.ldc * ce;
+        if (p.R) b.R = (const char*)p.R + m0 * g.ldc * 2;
+        hipError_t e = run(a, true);
+        return e != hipSuccess ? e : run(b, false);
+      }
+    }
   }
-  return big ? dispatch_layout<256, 256, bf16_t>(g.layout, p, g.batch, s)
-             : dispatch_layout<128, 128, bf16_t>(g.layout, p, g.batch, s);
+  return run(p, big);
 }
 
 }  // namespace tbp

@@ -27,6 +27,7 @@ def _say(msg):
 # ------------------------------------------------------------------------------------------- GEMM
 GEMM_SHAPES = [  # (M, N, K): several tiles plus ragged tails in every dimension (multiples of 8 for bf16)
     (256, 256, 64), (520, 392, 200), (1000, 136, 72), (136, 1000, 328), (264, 520, 1096), (8, 8, 8),
+    (4096, 4344, 72), (4344, 4096, 40),     # 272 large tiles: the output is cut into whole rounds + a small-tile rest
 ]
 
 
