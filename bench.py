@@ -217,6 +217,29 @@ def kernel_rates(shape, tbp, torch, dev, tdt) -> dict:
                      "bytes": nbytes, "buffer_sets": nset}
 
     L = tbp.lib()
+    # references that price the machine, not the method: a plain device copy and a register-resident MFMA loop
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src); torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(4):
+        dst.copy_(src)
+    b.record(); torch.cuda.synchronize()
+    res["device_copy_reference"] = {"GB/s": round(2 * (1 << 30) * 4 / (a.elapsed_time(b) * 1e-3) / 1e9, 1),
+                                    "what": "torch copy_ of 1 GiB (read + write counted)"}
+    del src, dst
+    seed = torch.randn(4096, device=dev).to(torch.bfloat16)
+    sink = torch.empty(1024 * 256, device=dev, dtype=torch.float32)
+    blocks, iters = 1024, 4096
+    L.tbp_mfma_ceiling(blocks, 64, seed.data_ptr(), sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(3):
+        L.tbp_mfma_ceiling(blocks, iters, seed.data_ptr(), sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    b.record(); torch.cuda.synchronize()
+    res["mfma_loop_reference"] = {"TFLOP/s": round(3 * blocks * iters * 2.0 ** 21 / (a.elapsed_time(b) * 1e-3) / 1e12, 1),
+                                  "what": "register-resident 32x32x16 bf16 MFMA loop, 4 waves per CU, ~7 ms"}
     import ctypes as C
     stream = torch.cuda.current_stream().cuda_stream
     dt = tbp.TBP_BF16 if shape.dtype == "bf16" else tbp.TBP_F32

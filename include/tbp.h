@@ -171,6 +171,12 @@ tbp_status tbp_rope(int dtype, int rows, int seq, int n_heads, int head_dim, int
 tbp_status tbp_softmax_fwd(int dtype, int n_mat, int seq, int causal, const float* scores, void* P, void* stream);
 tbp_status tbp_softmax_p1(int dtype, int n_mat, int seq, int causal, const void* P, void* dP_dS, void* stream);
 
+/* Measurement aid (no paper passage: it prices the hardware, not the method): a register-resident loop of
+ * 32x32x16 bf16 MFMAs, blocks x 4 wavefronts x iters x 16 instructions = blocks*iters*2^21 FLOP, touching no memory
+ * inside the loop.  What it sustains is the practical ceiling of the matrix pipes under the chip's power management.
+ * seed: device, 4096 bf16 values (any finite data); sink: device, blocks*256 floats (written once). */
+tbp_status tbp_mfma_ceiling(int blocks, int iters, const void* seed, float* sink, void* stream);
+
 const char* tbp_last_error(void);
 /* Library version string (static storage). */
 const char* tbp_version(void);

@@ -88,6 +88,7 @@ def lib() -> C.CDLL:
         L.tbp_stage_backward_p2.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.tbp_stage_stash_stats.argtypes = [C.c_void_p, C.POINTER(_tbp_stash_stats)]
         L.tbp_stage_reset.argtypes = [C.c_void_p]
+        L.tbp_mfma_ceiling.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.tbp_rmsnorm_p1_scratch_bytes.argtypes = [C.c_int]
         L.tbp_rope_table_bytes.argtypes = [C.c_int, C.c_int]
         _lib = L

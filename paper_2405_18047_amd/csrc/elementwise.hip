@@ -145,19 +145,33 @@ __global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float 
     for (int i = 0; i < N; i++) cacc[c][i] = 0.f;
   const int stride = G * gridDim.x;
   const int iters = (rows + stride - 1) / stride;
+  // rows are double-buffered in registers: the next row's x, dy and residual are requested before the current
+  // row is reduced, so a memory latency is paid once per workgroup, not once per row
+  Raw xn[MAXC], yn[MAXC], rn[MAXC];
+  auto fetch = [&](int it) {
+    const int row = (it * (int)gridDim.x + (int)blockIdx.x) * G + grp;
+    if (it < iters && row < rows) {
+      const long base = (long)row * d;
+#pragma unroll
+      for (int c = 0; c < MAXC; c++) {
+        const int ch = t + TPR * c;
+        if (ch < nchunk) {
+          xn[c] = Vec<T>::load_raw(x + base + ch * N);
+          yn[c] = Vec<T>::load_raw(dy + base + ch * N);
+          if (resid) rn[c] = Vec<T>::load_raw(resid + base + ch * N);
+        }
+      }
+    }
+  };
+  fetch(0);
   for (int it = 0; it < iters; it++) {
     const int row = (it * (int)gridDim.x + (int)blockIdx.x) * G + grp;
     const bool live = row < rows;
     const long base = (long)row * d;
-    Raw xr[MAXC], yr[MAXC];
+    Raw xr[MAXC], yr[MAXC], rr[MAXC];
 #pragma unroll
-    for (int c = 0; c < MAXC; c++) {
-      const int ch = t + TPR * c;
-      if (live && ch < nchunk) {
-        xr[c] = Vec<T>::load_raw(x + base + ch * N);
-        yr[c] = Vec<T>::load_raw(dy + base + ch * N);
-      }
-    }
+    for (int c = 0; c < MAXC; c++) { xr[c] = xn[c]; yr[c] = yn[c]; rr[c] = rn[c]; }
+    fetch(it + 1);
     // the gain vector is a few KiB and is re-read from the caches for every row: hiding the pointer from the
     // optimiser keeps it from hoisting MAXC more live vectors per lane out of the row loop
     const T* gp = g;
@@ -204,7 +218,7 @@ __global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float 
         Vec<T>::unpack(xr[c], xv);
         Vec<T>::unpack(yr[c], yv);
         Vec<T>::load(gp + ch * N, gv);
-        if (resid) Vec<T>::load(resid + base + ch * N, o);
+        if (resid) Vec<T>::unpack(rr[c], o);
         else {
 #pragma unroll
           for (int i = 0; i < N; i++) o[i] = 0.f;
@@ -315,133 +329,204 @@ __global__ void rope_table_kernel(int seq, int half, float base, float2* __restr
   table[idx] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
+// A thread owns one 16-byte column chunk of the rotation table row of its token (cos, sin kept in registers) and
+// applies it to kRopeHeads consecutive heads, so the table is read once per 8 heads instead of once per head.
+constexpr int kRopeHeads = 8;
 template <typename T>
-__global__ __launch_bounds__(256) void rope_kernel(long nvec, int seq, int n_heads, int head_dim, long ld,
+__global__ __launch_bounds__(256) void rope_kernel(long nitems, int seq, int n_heads, int head_dim, long ld,
                                                    const float2* __restrict__ table, float sgn, T* __restrict__ x) {
   constexpr int N = Vec<T>::N;
   const int half = head_dim / 2;
   const int cph = half / N;                   // chunks per head half
-  for (long v = blockIdx.x * 256L + threadIdx.x; v < nvec; v += 256L * gridDim.x) {
+  const int ngrp = (n_heads + kRopeHeads - 1) / kRopeHeads;
+  for (long v = blockIdx.x * 256L + threadIdx.x; v < nitems; v += 256L * gridDim.x) {
     const int c = (int)(v % cph);
-    const long hv = v / cph;
-    const int h = (int)(hv % n_heads);
-    const long row = hv / n_heads;
+    const long gv = v / cph;
+    const int hg = (int)(gv % ngrp);
+    const long row = gv / ngrp;
     const int pos = (int)(row % seq);
-    T* pa = x + row * ld + (long)h * head_dim + c * N;
-    T* pb = pa + half;
-    float a[N], b[N], oa[N], ob[N];
-    Vec<T>::load(pa, a);
-    Vec<T>::load(pb, b);
+    float cs[N], sn[N];
     const float2* tb = table + (long)pos * half + c * N;
 #pragma unroll
     for (int i = 0; i < N; i++) {
-      const float2 cs = tb[i];
-      const float sn = cs.y * sgn;
-      oa[i] = a[i] * cs.x - b[i] * sn;
-      ob[i] = a[i] * sn + b[i] * cs.x;
+      const float2 t = tb[i];
+      cs[i] = t.x;
+      sn[i] = t.y * sgn;
     }
-    Vec<T>::store(pa, oa);
-    Vec<T>::store(pb, ob);
+    const int h0 = hg * kRopeHeads;
+    const int hn = (n_heads - h0) < kRopeHeads ? (n_heads - h0) : kRopeHeads;
+    T* base = x + row * ld + (long)h0 * head_dim + c * N;
+#pragma unroll 4
+    for (int u = 0; u < hn; u++) {
+      T* pa = base + (long)u * head_dim;
+      T* pb = pa + half;
+      float a[N], b[N], oa[N], ob[N];
+      Vec<T>::load(pa, a);
+      Vec<T>::load(pb, b);
+#pragma unroll
+      for (int i = 0; i < N; i++) {
+        oa[i] = a[i] * cs[i] - b[i] * sn[i];
+        ob[i] = a[i] * sn[i] + b[i] * cs[i];
+      }
+      Vec<T>::store(pa, oa);
+      Vec<T>::store(pb, ob);
+    }
   }
 }
 
 // ---- softmax ------------------------------------------------------------------------------------------
-// One wavefront per row.  Row `i` of a causal matrix has i+1 live columns; the written row is zero-filled
-// up to the next multiple of kCausalPad (the products that consume it skip everything beyond that).
+// One wavefront per PAIR of rows (i, S-1-i) of one matrix.  Row i of a causal matrix has i+1 live columns, so the
+// two rows of a pair hold S+1 live elements between them whatever i is: every wave does the same amount of work
+// and no wave is left with a handful of active lanes.  The pair is walked as one stream of 16-byte chunks, first
+// row A's, then row B's; each chunk knows its row, so the two row reductions are two wavefront reductions over
+// the same registers.  A written row is zero-filled from the diagonal up to the next multiple of kCausalPad
+// columns (the products that consume it skip everything beyond that).
+struct RowPair {
+  long rowA, rowB;      // global row indices (matrix * seq + row)
+  int liveA, liveB;     // live columns
+  int nA, nAB;          // chunks (of N elements) written for row A, and for both rows
+};
+template <int N>
+__device__ __forceinline__ RowPair row_pair(long pair, int seq, int causal) {
+  const int half = seq / 2;
+  const long mat = pair / half;
+  const int i = (int)(pair - mat * half);
+  RowPair r;
+  r.rowA = mat * seq + i;
+  r.rowB = mat * seq + (seq - 1 - i);
+  r.liveA = causal ? i + 1 : seq;
+  r.liveB = causal ? seq - i : seq;
+  int fa = (r.liveA + kCausalPad - 1) / kCausalPad * kCausalPad, fb = (r.liveB + kCausalPad - 1) / kCausalPad * kCausalPad;
+  if (fa > seq) fa = seq;
+  if (fb > seq) fb = seq;
+  r.nA = fa / N;
+  r.nAB = r.nA + fb / N;
+  return r;
+}
+
 template <typename T, int MAXC>
-__global__ __launch_bounds__(256) void softmax_fwd_kernel(long nrows, int seq, int causal,
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(long npairs, int seq, int causal,
                                                           const float* __restrict__ scores, T* __restrict__ P) {
-  const long row = blockIdx.x * 4L + (threadIdx.x >> 6);
-  if (row >= nrows) return;
+  const long pair = blockIdx.x * 4L + (threadIdx.x >> 6);
+  if (pair >= npairs) return;
   const int lane = threadIdx.x & 63;
-  const int i = (int)(row % seq);
-  const int live = causal ? i + 1 : seq;
-  int fill = (live + kCausalPad - 1) / kCausalPad * kCausalPad;
-  if (fill > seq) fill = seq;
-  const float* s = scores + row * seq;
+  const RowPair rp = row_pair<4>(pair, seq, causal);
   float v[MAXC][4];
-  float mx = -INFINITY;
+  float mxA = -INFINITY, mxB = -INFINITY;
 #pragma unroll
   for (int c = 0; c < MAXC; c++) {
-    const int col = (lane + 64 * c) * 4;
-    if (col < live) {
-      Vec<float>::load(s + col, v[c]);
+    const int u = lane + 64 * c;
+    const bool isB = u >= rp.nA;
+    const int col = (isB ? u - rp.nA : u) * 4;
+    const int live = isB ? rp.liveB : rp.liveA;
+    if (u < rp.nAB && col < live) {
+      Vec<float>::load(scores + (isB ? rp.rowB : rp.rowA) * seq + col, v[c]);
+      float m = -INFINITY;
 #pragma unroll
       for (int e = 0; e < 4; e++) {
         if (col + e >= live) v[c][e] = -INFINITY;
-        mx = fmaxf(mx, v[c][e]);
+        m = fmaxf(m, v[c][e]);
       }
+      if (isB) mxB = fmaxf(mxB, m); else mxA = fmaxf(mxA, m);
     }
   }
-  mx = wave_max(mx);
-  float sum = 0.f;
+  mxA = wave_max(mxA);
+  mxB = wave_max(mxB);
+  float sumA = 0.f, sumB = 0.f;
 #pragma unroll
   for (int c = 0; c < MAXC; c++) {
-    const int col = (lane + 64 * c) * 4;
-    if (col < live) {
+    const int u = lane + 64 * c;
+    const bool isB = u >= rp.nA;
+    const int col = (isB ? u - rp.nA : u) * 4;
+    const int live = isB ? rp.liveB : rp.liveA;
+    if (u < rp.nAB && col < live) {
+      const float mx = isB ? mxB : mxA;
+      float t = 0.f;
 #pragma unroll
       for (int e = 0; e < 4; e++) {
         v[c][e] = __expf(v[c][e] - mx);
-        sum += v[c][e];
+        t += v[c][e];
       }
+      if (isB) sumB += t; else sumA += t;
     }
   }
-  sum = wave_sum(sum);
-  const float inv = 1.f / sum;
-  T* o = P + row * seq;
+  sumA = wave_sum(sumA);
+  sumB = wave_sum(sumB);
+  const float invA = 1.f / sumA, invB = 1.f / sumB;
 #pragma unroll
   for (int c = 0; c < MAXC; c++) {
-    const int col = (lane + 64 * c) * 4;
-    if (col < fill) {
+    const int u = lane + 64 * c;
+    const bool isB = u >= rp.nA;
+    const int col = (isB ? u - rp.nA : u) * 4;
+    const int live = isB ? rp.liveB : rp.liveA;
+    if (u < rp.nAB) {
+      T* o = P + (isB ? rp.rowB : rp.rowA) * seq + col;
+      const float inv = isB ? invB : invA;
       if (col < live) {
 #pragma unroll
-        for (int e = 0; e < 4; e++) o[col + e] = (T)(v[c][e] * inv);
+        for (int e = 0; e < 4; e++) o[e] = (T)(v[c][e] * inv);
       } else {
 #pragma unroll
-        for (int e = 0; e < 4; e++) o[col + e] = (T)0.f;
+        for (int e = 0; e < 4; e++) o[e] = (T)0.f;
       }
     }
   }
 }
 
-// dS = P * (dP - sum_j dP_j P_j), in place over dP; same zero-fill rule.
+// dS = P * (dP - sum_j dP_j P_j), in place over dP; same pairing and zero-fill rule.
 template <typename T, int MAXC>
-__global__ __launch_bounds__(256) void softmax_p1_kernel(long nrows, int seq, int causal, const T* __restrict__ P,
+__global__ __launch_bounds__(256) void softmax_p1_kernel(long npairs, int seq, int causal, const T* __restrict__ P,
                                                          T* __restrict__ dP) {
   constexpr int N = Vec<T>::N;
-  const long row = blockIdx.x * 4L + (threadIdx.x >> 6);
-  if (row >= nrows) return;
+  typedef typename Vec<T>::Raw Raw;
+  const long pair = blockIdx.x * 4L + (threadIdx.x >> 6);
+  if (pair >= npairs) return;
   const int lane = threadIdx.x & 63;
-  const int i = (int)(row % seq);
-  const int live = causal ? i + 1 : seq;
-  int fill = (live + kCausalPad - 1) / kCausalPad * kCausalPad;
-  if (fill > seq) fill = seq;
-  const T* p = P + row * seq;
-  T* g = dP + row * seq;
-  float pv[MAXC][N], gv[MAXC][N];
-  float dot = 0.f;
+  const RowPair rp = row_pair<N>(pair, seq, causal);
+  Raw pr[MAXC], gr[MAXC];
+  float dotA = 0.f, dotB = 0.f;
 #pragma unroll
   for (int c = 0; c < MAXC; c++) {
-    const int col = (lane + 64 * c) * N;
-    if (col < live) {
-      Vec<T>::load(p + col, pv[c]);
-      Vec<T>::load(g + col, gv[c]);
+    const int u = lane + 64 * c;
+    const bool isB = u >= rp.nA;
+    const int col = (isB ? u - rp.nA : u) * N;
+    const int live = isB ? rp.liveB : rp.liveA;
+    if (u < rp.nAB && col < live) {
+      const long off = (isB ? rp.rowB : rp.rowA) * seq + col;
+      pr[c] = Vec<T>::load_raw(P + off);
+      gr[c] = Vec<T>::load_raw(dP + off);
+      float pv[N], gv[N];
+      Vec<T>::unpack(pr[c], pv);
+      Vec<T>::unpack(gr[c], gv);
+      float t = 0.f;
 #pragma unroll
-      for (int e = 0; e < N; e++) {
-        if (col + e >= live) { pv[c][e] = 0.f; gv[c][e] = 0.f; }
-        dot += pv[c][e] * gv[c][e];
-      }
+      for (int e = 0; e < N; e++)
+        if (col + e < live) t += pv[e] * gv[e];
+      if (isB) dotB += t; else dotA += t;
     }
   }
-  dot = wave_sum(dot);
+  dotA = wave_sum(dotA);
+  dotB = wave_sum(dotB);
 #pragma unroll
   for (int c = 0; c < MAXC; c++) {
-    const int col = (lane + 64 * c) * N;
-    if (col < fill) {
+    const int u = lane + 64 * c;
+    const bool isB = u >= rp.nA;
+    const int col = (isB ? u - rp.nA : u) * N;
+    const int live = isB ? rp.liveB : rp.liveA;
+    if (u < rp.nAB) {
       float o[N];
+      if (col < live) {
+        const float dot = isB ? dotB : dotA;
+        float pv[N], gv[N];
+        Vec<T>::unpack(pr[c], pv);
+        Vec<T>::unpack(gr[c], gv);
 #pragma unroll
-      for (int e = 0; e < N; e++) o[e] = (col < live) ? pv[c][e] * (gv[c][e] - dot) : 0.f;
-      Vec<T>::store(g + col, o);
+        for (int e = 0; e < N; e++) o[e] = (col + e < live) ? pv[e] * (gv[e] - dot) : 0.f;
+      } else {
+#pragma unroll
+        for (int e = 0; e < N; e++) o[e] = 0.f;
+      }
+      Vec<T>::store(dP + (isB ? rp.rowB : rp.rowA) * seq + col, o);
     }
   }
 }
@@ -562,7 +647,7 @@ hipError_t rope(int dtype, int rows, int seq, int n_heads, int head_dim, long ld
                 void* x, hipStream_t s) {
   if (rows <= 0 || n_heads <= 0) return hipSuccess;
   const int n = dtype ? 8 : 4;
-  const long nvec = (long)rows * n_heads * (head_dim / 2 / n);
+  const long nvec = (long)rows * ((n_heads + kRopeHeads - 1) / kRopeHeads) * (head_dim / 2 / n);
   const float sgn = inverse ? -1.f : 1.f;
   if (dtype) hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3(grid_for(nvec)), dim3(256), 0, s, nvec, seq, n_heads,
                                 head_dim, ld, table, sgn, (bf16_t*)x);
@@ -571,35 +656,51 @@ hipError_t rope(int dtype, int rows, int seq, int n_heads, int head_dim, long ld
   return hipGetLastError();
 }
 
+// chunks per lane needed for a row pair: the two zero-filled rows hold at most min(2 S, S + 2 * kCausalPad) elements
+static inline int pair_chunks(int seq, int causal, int n) {
+  long el = causal ? (long)seq + 2 * kCausalPad : 2L * seq;
+  if (el > 2L * seq) el = 2L * seq;
+  return (int)((el / n + 63) / 64);
+}
+#define TBP_PICK_MAXC(KERNEL, ...)                                                                           \
+  do {                                                                                                       \
+    if (c <= 2) hipLaunchKernelGGL((KERNEL<T, 2>), grid, dim3(256), 0, s, __VA_ARGS__);                       \
+    else if (c <= 3) hipLaunchKernelGGL((KERNEL<T, 3>), grid, dim3(256), 0, s, __VA_ARGS__);                  \
+    else if (c <= 5) hipLaunchKernelGGL((KERNEL<T, 5>), grid, dim3(256), 0, s, __VA_ARGS__);                  \
+    else if (c <= 8) hipLaunchKernelGGL((KERNEL<T, 8>), grid, dim3(256), 0, s, __VA_ARGS__);                  \
+    else if (c <= 10) hipLaunchKernelGGL((KERNEL<T, 10>), grid, dim3(256), 0, s, __VA_ARGS__);                \
+    else if (c <= 18) hipLaunchKernelGGL((KERNEL<T, 18>), grid, dim3(256), 0, s, __VA_ARGS__);                \
+    else if (c <= 32) hipLaunchKernelGGL((KERNEL<T, 32>), grid, dim3(256), 0, s, __VA_ARGS__);                \
+    else return hipErrorInvalidValue;                                                                        \
+  } while (0)
+
 template <typename T>
 static hipError_t softmax_fwd_t(long nrows, int seq, int causal, const float* sc, void* P, hipStream_t s) {
-  const int c = (seq / 4 + 63) / 64;
-  const dim3 grid((unsigned)((nrows + 3) / 4));
-  if (c <= 4) hipLaunchKernelGGL((softmax_fwd_kernel<T, 4>), grid, dim3(256), 0, s, nrows, seq, causal, sc, (T*)P);
-  else if (c <= 8) hipLaunchKernelGGL((softmax_fwd_kernel<T, 8>), grid, dim3(256), 0, s, nrows, seq, causal, sc, (T*)P);
-  else if (c <= 16) hipLaunchKernelGGL((softmax_fwd_kernel<T, 16>), grid, dim3(256), 0, s, nrows, seq, causal, sc, (T*)P);
-  else return hipErrorInvalidValue;
+  const int c = pair_chunks(seq, causal, 4);
+  const long npairs = nrows / 2;
+  const dim3 grid((unsigned)((npairs + 3) / 4));
+  TBP_PICK_MAXC(softmax_fwd_kernel, npairs, seq, causal, sc, (T*)P);
   return hipGetLastError();
 }
 hipError_t softmax_fwd(int dtype, long nrows, int seq, int causal, const float* scores, void* P, hipStream_t s) {
   if (nrows <= 0) return hipSuccess;
+  if (seq % 2) return hipErrorInvalidValue;       // rows are processed in pairs (i, seq-1-i)
   return dtype ? softmax_fwd_t<bf16_t>(nrows, seq, causal, scores, P, s)
                : softmax_fwd_t<float>(nrows, seq, causal, scores, P, s);
 }
 
 template <typename T>
 static hipError_t softmax_p1_t(long nrows, int seq, int causal, const void* P, void* dP, hipStream_t s) {
-  const int c = (seq / Vec<T>::N + 63) / 64;
-  const dim3 grid((unsigned)((nrows + 3) / 4));
-  if (c <= 2) hipLaunchKernelGGL((softmax_p1_kernel<T, 2>), grid, dim3(256), 0, s, nrows, seq, causal, (const T*)P, (T*)dP);
-  else if (c <= 4) hipLaunchKernelGGL((softmax_p1_kernel<T, 4>), grid, dim3(256), 0, s, nrows, seq, causal, (const T*)P, (T*)dP);
-  else if (c <= 8) hipLaunchKernelGGL((softmax_p1_kernel<T, 8>), grid, dim3(256), 0, s, nrows, seq, causal, (const T*)P, (T*)dP);
-  else if (c <= 16) hipLaunchKernelGGL((softmax_p1_kernel<T, 16>), grid, dim3(256), 0, s, nrows, seq, causal, (const T*)P, (T*)dP);
-  else return hipErrorInvalidValue;
+  const int c = pair_chunks(seq, causal, Vec<T>::N);
+  const long npairs = nrows / 2;
+  const dim3 grid((unsigned)((npairs + 3) / 4));
+  TBP_PICK_MAXC(softmax_p1_kernel, npairs, seq, causal, (const T*)P, (T*)dP);
   return hipGetLastError();
 }
+#undef TBP_PICK_MAXC
 hipError_t softmax_p1(int dtype, long nrows, int seq, int causal, const void* P, void* dP, hipStream_t s) {
   if (nrows <= 0) return hipSuccess;
+  if (seq % 2) return hipErrorInvalidValue;
   return dtype ? softmax_p1_t<bf16_t>(nrows, seq, causal, P, dP, s) : softmax_p1_t<float>(nrows, seq, causal, P, dP, s);
 }
 

@@ -387,6 +387,48 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   }
 }
 
+// ------------------------------------------------------------------------------------------ ceiling
+// Register-resident MFMA loop: 4 waves per compute unit, 16 independent 32x32x16 bf16 MFMAs per iteration on
+// operands that never leave the registers.  It measures what the matrix pipes sustain under the chip's power
+// management with no memory system involved: the practical ceiling the GEMM kernel is compared with.
+__global__ __launch_bounds__(256) void mfma_ceiling_kernel(int iters, const bf16_t* __restrict__ seed,
+                                                           float* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    a[i] = *reinterpret_cast<const bf16x8*>(seed + (size_t)(i * 64 + lane) * 8);
+    b[i] = *reinterpret_cast<const bf16x8*>(seed + (size_t)((4 + i) * 64 + lane) * 8);
+  }
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+  for (int it = 0; it < iters; it++) {
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int j = 0; j < 4; j++)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) t += acc[i][j][e];
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = t;
+}
+
+hipError_t mfma_ceiling(int blocks, int iters, const void* seed, float* sink, hipStream_t s) {
+  hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(blocks), dim3(256), 0, s, iters, (const bf16_t*)seed, sink);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------ fp32
 // 64 x 64 x 16 tile, 256 threads, 4 x 4 outputs per thread; operands addressed through element strides so
 // one kernel serves NN, NT and TN.

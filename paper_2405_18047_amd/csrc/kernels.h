@@ -63,6 +63,10 @@ hipError_t softmax_p1(int dtype, long n_rows_total, int seq, int causal, const v
 hipError_t gain_grad_sum(const float* parts, const int* rows_host, int n, int d, int accumulate, float* out,
                          hipStream_t s);
 
+// Register-resident MFMA loop (measurement aid): blocks x 4 waves x iters x 16 MFMAs of 32x32x16.
+// seed: 8 x 64 x 8 bf16 values; sink: blocks * 256 floats.
+hipError_t mfma_ceiling(int blocks, int iters, const void* seed, float* sink, hipStream_t s);
+
 // Limits enforced by the host before any launch.
 inline int max_d_model(int dtype) { return dtype == 1 ? 8192 : 4096; }
 constexpr int kMaxSeq = 4096;

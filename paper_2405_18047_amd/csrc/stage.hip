@@ -549,6 +549,12 @@ tbp_status tbp_gemm(int dtype, int layout, int M, int N, int K, float alpha, con
   return TBP_OK;
 }
 
+tbp_status tbp_mfma_ceiling(int blocks, int iters, const void* seed, float* sink, void* stream) {
+  if (blocks < 1 || blocks > 65536 || iters < 0 || !seed || !sink) return fail(TBP_EINVAL, "bad mfma ceiling arguments");
+  TBP_HIP(tbp::mfma_ceiling(blocks, iters, seed, sink, static_cast<hipStream_t>(stream)));
+  return TBP_OK;
+}
+
 tbp_status tbp_rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, const void* g, void* y, void* stream) {
   if (check_dtype(dtype) != TBP_OK) return TBP_EINVAL;
   if (rows < 0 || d < 1 || d % vecq(dtype) || d > tbp::max_d_model(dtype)) return fail(TBP_EINVAL, "bad rows / d");
