@@ -277,20 +277,29 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   // stall MFMAs on reads they do not need): the last iteration also fetches "tile nk" fragments, stale but
   // in-bounds LDS contents that are never used.
   constexpr int MM = TM * TN, UNITS = TM + TN;
+  // Fragment fetch order = order of first use by the MFMA sequence (i-major): a0, then every b, then a1, a2, ...;
+  // one fetch per MFMA from the start of the region, so the fragments the NEXT region needs first have the whole
+  // region to arrive and the last fetches still have MM - UNITS MFMAs of cover.  The copies fill the second half.
   auto region = [&](const bf16x8* fa, const bf16x8* fb, bf16x8* na, bf16x8* nb, int nt, int nks, const CopyJob* job) {
     lds_u8* const st = lds + (nt % STAGES) * STAGE_BYTES;
 #pragma unroll
     for (int m = 0; m < MM; m++) {
       const int i = m / TN, j = m % TN;
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      constexpr int UPM = (UNITS + MM - 1) / MM;           // fetches per MFMA (1 for the tiles used here)
 #pragma unroll
-      for (int u = (m * UNITS) / MM; u < ((m + 1) * UNITS) / MM; u++) {
-        if (u < TM) na[u] = read_frag<BM, AKC>(st + a_base[TA::variant(nks, u)] + TA::frag_step(nks, u));
-        else nb[u - TM] = read_frag<BN, BKC>(st + b_base[TB::variant(nks, u - TM)] + TB::frag_step(nks, u - TM));
+      for (int q = 0; q < UPM; q++) {
+        const int u = m * UPM + q;                         // position in the fetch order
+        if (u < UNITS) {
+          if (u == 0) na[0] = read_frag<BM, AKC>(st + a_base[TA::variant(nks, 0)] + TA::frag_step(nks, 0));
+          else if (u <= TN) nb[u - 1] = read_frag<BN, BKC>(st + b_base[TB::variant(nks, u - 1)] + TB::frag_step(nks, u - 1));
+          else na[u - TN] = read_frag<BM, AKC>(st + a_base[TA::variant(nks, u - TN)] + TA::frag_step(nks, u - TN));
+        }
       }
       if (job) {
+        constexpr int C0 = MM >= 2 * L ? MM - L : 0;       // first MFMA that carries a copy
 #pragma unroll
-        for (int c = (m * L) / MM; c < ((m + 1) * L) / MM; c++) copy_one(*job, c);
+        for (int c = ((m - C0) * L) / (MM - C0); m >= C0 && c < ((m - C0 + 1) * L) / (MM - C0); c++) copy_one(*job, c);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
