@@ -531,6 +531,33 @@ __global__ __launch_bounds__(256) void softmax_p1_kernel(long npairs, int seq, i
   }
 }
 
+// ---- per-head row dot products: delta[t, h] = sum_c a[t, h*dh + c] * b[t, h*dh + c] -----------------------------
+// (the row sums rowsum(dP * P) of the softmax backward equal rowsum(do * o), which needs no S x S tensor).
+// One 256-thread workgroup per token row: 16-byte chunk products to LDS, then one thread per head adds its chunks.
+template <typename T>
+__global__ __launch_bounds__(256) void head_rowdot_kernel(int n_heads, int head_dim, const T* __restrict__ a,
+                                                          const T* __restrict__ b, float* __restrict__ delta) {
+  constexpr int N = Vec<T>::N;
+  extern __shared__ float part[];             // [d / N]
+  const long row = blockIdx.x;
+  const int d = n_heads * head_dim, nchunk = d / N, cph = head_dim / N;
+  for (int ch = threadIdx.x; ch < nchunk; ch += 256) {
+    float x[N], y[N];
+    Vec<T>::load(a + row * d + ch * N, x);
+    Vec<T>::load(b + row * d + ch * N, y);
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < N; i++) t += x[i] * y[i];
+    part[ch] = t;
+  }
+  __syncthreads();
+  for (int h = threadIdx.x; h < n_heads; h += 256) {
+    float t = 0.f;
+    for (int c = 0; c < cph; c++) t += part[h * cph + c];
+    delta[row * n_heads + h] = t;
+  }
+}
+
 // ------------------------------------------------------------------------------------------ host
 static inline int chunks_per_thread(int d, int n) { return (d / n + 255) / 256; }
 
@@ -702,6 +729,18 @@ hipError_t softmax_p1(int dtype, long nrows, int seq, int causal, const void* P,
   if (nrows <= 0) return hipSuccess;
   if (seq % 2) return hipErrorInvalidValue;
   return dtype ? softmax_p1_t<bf16_t>(nrows, seq, causal, P, dP, s) : softmax_p1_t<float>(nrows, seq, causal, P, dP, s);
+}
+
+hipError_t head_rowdot(int dtype, int rows, int n_heads, int head_dim, const void* a, const void* b, float* delta,
+                       hipStream_t s) {
+  if (rows <= 0 || n_heads <= 0) return hipSuccess;
+  const int n = dtype ? 8 : 4;
+  const size_t smem = (size_t)(n_heads * head_dim / n) * sizeof(float);
+  if (dtype) hipLaunchKernelGGL(head_rowdot_kernel<bf16_t>, dim3(rows), dim3(256), smem, s, n_heads, head_dim,
+                                (const bf16_t*)a, (const bf16_t*)b, delta);
+  else hipLaunchKernelGGL(head_rowdot_kernel<float>, dim3(rows), dim3(256), smem, s, n_heads, head_dim,
+                          (const float*)a, (const float*)b, delta);
+  return hipGetLastError();
 }
 
 }  // namespace tbp

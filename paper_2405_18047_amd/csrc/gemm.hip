@@ -39,6 +39,9 @@ struct GemmParams {
   int causal;
   // fp32 kernel only: element strides of A(m,k) and B(k,n)
   long sam, sak, sbk, sbn;
+  // fused softmax backward (see GemmArgs)
+  const float* delta; long ldd, sDo, sDi;
+  int delta_causal;
 };
 
 constexpr int BK = 32;                     // contraction depth of one LDS slot
@@ -356,42 +359,67 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
 #pragma unroll
       for (int e = 0; e < 16; e++)
         strip[(8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * SW + j * 32 + (lane & 31)] = p.alpha * acc[i][j][e];
+    // what the strip needs from memory (old C for +=, residual or probabilities) is requested for the whole strip
+    // first, so the stores below wait for one memory latency per strip instead of one per row group
+    constexpr int NIT = 32 / RPI, GRP = NIT < 8 ? NIT : 8;    // row groups per strip, and per request batch
+    const bool need_pre = (sizeof(OutT) == 4) ? false : (R != nullptr);   // (fp32 += reads its old value in place)
+    __builtin_amdgcn_sched_barrier(0);      // keep the next strip's requests from being hoisted over this one
 #pragma unroll
-    for (int it = 0; it < 32 / RPI; it++) {
-      const int r = it * RPI + sr;
-      const int grow = m0 + wm * WM + i * 32 + r;
-      if (grow < p.M && gcol < p.N) {       // N is a multiple of 8: a vector is inside or outside as a whole
-        const long idx = (long)grow * p.ldc + gcol;
-        float v[V];
+    for (int g0 = 0; g0 < NIT; g0 += GRP) {
+      u32x4 pre[GRP];
+      float dl[GRP];
 #pragma unroll
-        for (int q = 0; q < V; q += 4) {
-          const f32x4 t4 = *reinterpret_cast<LDS_AS const f32x4*>(strip + r * SW + sc + q);
-          v[q] = t4[0]; v[q + 1] = t4[1]; v[q + 2] = t4[2]; v[q + 3] = t4[3];
-        }
-        if constexpr (sizeof(OutT) == 4) {
-          f32x4* dst = reinterpret_cast<f32x4*>(C + idx);
-          if (p.accumulate) {
-            const f32x4 o = *dst;
-            v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
-          }
-          f32x4 w4;
-          w4[0] = v[0]; w4[1] = v[1]; w4[2] = v[2]; w4[3] = v[3];
-          *dst = w4;
-        } else {
-          if (R) {
-            const u32x4 rr = *reinterpret_cast<const u32x4*>(R + idx);
-#pragma unroll
-            for (int q = 0; q < 4; q++) {
-              v[2 * q] += __uint_as_float(rr[q] << 16);
-              v[2 * q + 1] += __uint_as_float(rr[q] & 0xffff0000u);
-            }
-          }
-          bf16x8 o;
-#pragma unroll
-          for (int q = 0; q < 8; q++) o[q] = (bf16_t)v[q];
-          *reinterpret_cast<bf16x8*>(C + idx) = o;
+      for (int u = 0; u < GRP; u++) {
+        const int grow = m0 + wm * WM + i * 32 + (g0 + u) * RPI + sr;
+        if (need_pre && grow < p.M && gcol < p.N) {
+          const long idx = (long)grow * p.ldc + gcol;
+          pre[u] = *reinterpret_cast<const u32x4*>(R + idx);
+          if (p.delta) dl[u] = p.delta[zo * p.sDo + zi * p.sDi + (long)grow * p.ldd];
         }
       }
+#pragma unroll
+      for (int u = 0; u < GRP; u++) {
+        const int r = (g0 + u) * RPI + sr;
+        const int grow = m0 + wm * WM + i * 32 + r;
+        if (grow < p.M && gcol < p.N) {     // N is a multiple of 8: a vector is inside or outside as a whole
+          const long idx = (long)grow * p.ldc + gcol;
+          float v[V];
+#pragma unroll
+          for (int q = 0; q < V; q += 4) {
+            const f32x4 t4 = *reinterpret_cast<LDS_AS const f32x4*>(strip + r * SW + sc + q);
+            v[q] = t4[0]; v[q + 1] = t4[1]; v[q + 2] = t4[2]; v[q + 3] = t4[3];
+          }
+          if constexpr (sizeof(OutT) == 4) {
+            if (p.accumulate) {
+              const f32x4 o = *reinterpret_cast<const f32x4*>(C + idx);
+              v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
+            }
+            f32x4 w4;
+            w4[0] = v[0]; w4[1] = v[1]; w4[2] = v[2]; w4[3] = v[3];
+            *reinterpret_cast<f32x4*>(C + idx) = w4;
+          } else {
+            if (p.delta) {                  // dS = P * (dP - delta[row]); zero above the diagonal
+#pragma unroll
+              for (int q = 0; q < 4; q++) {
+                const float p0 = __uint_as_float(pre[u][q] << 16), p1 = __uint_as_float(pre[u][q] & 0xffff0000u);
+                v[2 * q] = (!p.delta_causal || gcol + 2 * q <= grow) ? p0 * (v[2 * q] - dl[u]) : 0.f;
+                v[2 * q + 1] = (!p.delta_causal || gcol + 2 * q + 1 <= grow) ? p1 * (v[2 * q + 1] - dl[u]) : 0.f;
+              }
+            } else if (R) {
+#pragma unroll
+              for (int q = 0; q < 4; q++) {
+                v[2 * q] += __uint_as_float(pre[u][q] << 16);
+                v[2 * q + 1] += __uint_as_float(pre[u][q] & 0xffff0000u);
+              }
+            }
+            bf16x8 o;
+#pragma unroll
+            for (int q = 0; q < 8; q++) o[q] = (bf16_t)v[q];
+            *reinterpret_cast<bf16x8*>(C + idx) = o;
+          }
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 }
@@ -504,8 +532,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
       if (col >= p.N) continue;
       const long idx = (long)row * p.ldc + col;
       float v = p.alpha * acc[i][j];
-      if (p.accumulate) v += C[idx];
-      if (R) v += R[idx];
+      if (p.delta) {
+        const float dl = p.delta[zo * p.sDo + zi * p.sDi + (long)row * p.ldd];
+        v = (!p.delta_causal || col <= row) ? R[idx] * (v - dl) : 0.f;
+      } else {
+        if (p.accumulate) v += C[idx];
+        if (R) v += R[idx];
+      }
       C[idx] = v;
     }
   }
@@ -554,6 +587,7 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.batch_inner = g.batch_inner > 0 ? g.batch_inner : 1;
   p.alpha = g.alpha; p.accumulate = g.accumulate; p.causal = g.causal;
+  p.delta = g.delta; p.ldd = g.ldd; p.sDo = g.sDo; p.sDi = g.sDi; p.delta_causal = g.delta_causal;
   if (dtype == 0) {
     switch (g.layout) {
       case NN: p.sam = g.lda; p.sak = 1; p.sbk = g.ldb; p.sbn = 1; break;
@@ -570,7 +604,9 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
   // bf16: large tiles when the output is big enough to fill 256 compute units with them
   const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
   const long tiles_big = (long)tiles_m * tiles_n * g.batch;
-  const bool big = g.M >= 256 && g.N >= 256 && tiles_big >= 192;
+  // short contractions (the per-head q k^T and do v^T, K = head_dim) are all prologue and epilogue: small tiles let
+  // two or three workgroups share a compute unit and overlap them
+  const bool big = g.M >= 256 && g.N >= 256 && tiles_big >= 192 && g.K > 256;
   auto run = [&](const GemmParams& q, bool use_big) -> hipError_t {
     if (g.out_f32)
       return use_big ? dispatch_layout<256, 256, float>(g.layout, q, g.batch, s)

@@ -33,6 +33,12 @@ struct GemmArgs {
   int batch_inner;
   long sAo, sAi, sBo, sBi, sCo, sCi;   // element strides of the outer / inner batch index
   int causal;            // Causal
+  // Softmax backward fused into the epilogue of dP = do v^T (per-head batched product with a storage-type output):
+  // when delta is set, R points at the probabilities P (same layout as C) and the kernel stores
+  // dS = P * (alpha * acc - delta[row]) for columns <= row and exact zeros above the diagonal (causal) instead of dP.
+  // delta[(zo * sDo + zi * sDi) + row * ldd] = rowsum(dP * P) = sum over the head's columns of do * o.
+  const float* delta; long ldd, sDo, sDi;
+  int delta_causal;
 };
 
 inline GemmArgs gemm_args(int layout, int M, int N, int K, const void* A, long lda, const void* B, long ldb,
@@ -58,6 +64,9 @@ hipError_t rope(int dtype, int rows, int seq, int n_heads, int head_dim, long ld
                 void* x, hipStream_t s);
 hipError_t softmax_fwd(int dtype, long n_rows_total, int seq, int causal, const float* scores, void* P, hipStream_t s);
 hipError_t softmax_p1(int dtype, long n_rows_total, int seq, int causal, const void* P, void* dP, hipStream_t s);
+// delta[t * n_heads + h] = sum_c a[t, h*dh + c] * b[t, h*dh + c]   (fp32; a, b are [rows, n_heads*head_dim])
+hipError_t head_rowdot(int dtype, int rows, int n_heads, int head_dim, const void* a, const void* b, float* delta,
+                       hipStream_t s);
 // out[d] (= or +=) sum over n of parts[n][d] given as n separate pointers packed in a device-free way:
 // parts are rows of one fp32 matrix, selected by index list held in kernel arguments (n <= 64 per launch).
 hipError_t gain_grad_sum(const float* parts, const int* rows_host, int n, int d, int accumulate, float* out,

@@ -77,7 +77,7 @@ struct Layout {
   size_t gain_part_bytes;
   size_t w_total, a_base, a_total, ws_base, ws_total, arena;
   // workspace pieces
-  size_t ws_t_f, ws_t_d0, ws_t_d1, ws_scores, ws_norm_partials, ws_rope;
+  size_t ws_t_f, ws_t_d0, ws_t_d1, ws_scores, ws_norm_partials, ws_rope, ws_delta;
   // accounting units
   size_t w_fwd_bytes_per_mb, w_p1_bytes_per_mb, a_bytes_per_mb;
 };
@@ -109,6 +109,7 @@ Layout plan(const Dims& c) {
   y.ws_scores = off; off += c.attn ? align_up((size_t)c.B * c.H * c.S * c.S * sizeof(float), 256) : 0;
   y.ws_norm_partials = off; off += align_up((size_t)tbp::kNormPartialBlocks * c.d * sizeof(float), 256);
   y.ws_rope = off; off += c.attn ? align_up((size_t)c.S * (c.dh / 2) * sizeof(float2), 256) : 0;
+  y.ws_delta = off; off += c.attn ? align_up((size_t)c.T * c.H * sizeof(float), 256) : 0;
   y.ws_total = off;
   y.arena = y.ws_base + y.ws_total;
   size_t fw = 0, p1 = 0;
@@ -292,16 +293,21 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
     void* P = st->aslot(l, A_P, slot);
     void* x0 = st->aslot(l, A_X0, slot);
     void* dqkv = st->wslab(l, W_DQKV, mb);
-    void* dP = st->ws(st->y.ws_scores);       // storage type, reuses the score workspace
+    void* dP = st->ws(st->y.ws_scores);       // dS, storage type, reuses the score workspace
     const float scale = 1.f / sqrtf((float)c.dh);
     const long hs = (long)c.S * c.S, bs = (long)c.H * hs, tok3 = (long)c.S * 3 * d;
     // da = dx1 Wo^T
     TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NT, T, d, d, dx1, d, st->w_o[l], d, da, d), s));
-    {  // dP = da v^T
+    // rowsum(dP * P) per (token, head) = rowsum(da * a): no S x S tensor needed for it
+    float* delta = (float*)st->ws(st->y.ws_delta);
+    TBP_HIP(tbp::head_rowdot(dt, T, c.H, c.dh, da, st->wslab(l, W_A, mb), delta, s));
+    {  // dS = P * (da v^T - delta): the softmax backward is the epilogue of the dP product (dP is never stored)
       GemmArgs g = head_gemm(c, tbp::NT, c.S, c.S, c.dh);
       g.A = da; g.lda = d; g.sAo = (long)c.S * d; g.sAi = c.dh;
       g.B = (const char*)qkv + (size_t)2 * d * c.e; g.ldb = 3 * d; g.sBo = tok3; g.sBi = c.dh;
       g.C = dP; g.ldc = c.S; g.sCo = bs; g.sCi = hs;
+      g.R = P;
+      g.delta = delta; g.ldd = c.H; g.sDo = (long)c.S * c.H; g.sDi = 1; g.delta_causal = c.causal;
       g.causal = c.causal ? tbp::CAUSAL_SKIP_UPPER : tbp::CAUSAL_NONE;
       TBP_HIP(tbp::gemm(dt, g, s));
     }
@@ -313,7 +319,6 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
       g.causal = c.causal ? tbp::CAUSAL_K_BEGIN : tbp::CAUSAL_NONE;
       TBP_HIP(tbp::gemm(dt, g, s));
     }
-    TBP_HIP(tbp::softmax_p1(dt, (long)c.B * c.H * c.S, c.S, c.causal, P, dP, s));
     {  // dq = dS k / sqrt(dh)
       GemmArgs g = head_gemm(c, tbp::NN, c.S, c.dh, c.S);
       g.alpha = scale;
