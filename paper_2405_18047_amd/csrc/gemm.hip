@@ -159,8 +159,9 @@ __device__ __forceinline__ bf16x8 read_frag(lds_u8* q) {
   }
 }
 
+// One output tile (tm_i, tn_i) of batch entry z of the product described by p.
 template <int BM, int BN, bool AKC, bool BKC, typename OutT>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
+__device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, int tn_i, int z) {
   constexpr int WM = BM / 2, WN = BN / 2;       // per-wave tile
   constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wave
   using TA = OperandTile<BM, AKC>;
@@ -178,26 +179,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
-  int tm_i, tn_i;
-  if (gridDim.z == 1) {
-    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm_i, tn_i);
-  } else {
-    // Batched (per-head) products: the causal variants do an amount of work that depends on the tile row, and the
-    // hardware hands consecutive workgroup ids to the 8 XCDs in turn, so a fixed id -> tile map would give one XCD
-    // all the long tiles of every head.  Rotating the map by the batch index spreads them evenly.
-    const int nt = (int)gridDim.x;
-    int id = ((int)blockIdx.x + 3 * (int)blockIdx.z) % nt;
-    if (p.causal == CAUSAL_SKIP_UPPER && p.tiles_m == p.tiles_n) {
-      // only the lower-triangular tiles are launched: id = tm (tm + 1) / 2 + tn
-      tm_i = (int)((__builtin_sqrtf(8.f * (float)id + 1.f) - 1.f) * 0.5f);
-      while (tm_i * (tm_i + 1) / 2 > id) tm_i--;
-      while ((tm_i + 1) * (tm_i + 2) / 2 <= id) tm_i++;
-      tn_i = id - tm_i * (tm_i + 1) / 2;
-    } else {
-      tm_i = id % p.tiles_m;
-      tn_i = id / p.tiles_m;
-    }
-  }
   const int m0 = tm_i * BM, n0 = tn_i * BN;
 
   int k_lo = 0, k_hi = p.K;
@@ -210,7 +191,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   }
   const int nk = (k_hi - k_lo + BK - 1) / BK;
 
-  const int z = blockIdx.z;
   const int zo = z / p.batch_inner, zi = z - zo * p.batch_inner;
   const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A) + zo * p.sAo + zi * p.sAi;
   const bf16_t* B = reinterpret_cast<const bf16_t*>(p.B) + zo * p.sBo + zi * p.sBi;
@@ -424,6 +404,61 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   }
 }
 
+template <int BM, int BN, bool AKC, bool BKC, typename OutT>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
+  int tm_i, tn_i;
+  if (gridDim.z == 1) {
+    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm_i, tn_i);
+  } else {
+    // Batched (per-head) products: the causal variants do an amount of work that depends on the tile row, and the
+    // hardware hands consecutive workgroup ids to the 8 XCDs in turn, so a fixed id -> tile map would give one XCD
+    // all the long tiles of every head.  Rotating the map by the batch index spreads them evenly.
+    const int nt = (int)gridDim.x;
+    int id = ((int)blockIdx.x + 3 * (int)blockIdx.z) % nt;
+    if (p.causal == CAUSAL_SKIP_UPPER && p.tiles_m == p.tiles_n) {
+      // only the lower-triangular tiles are launched: id = tm (tm + 1) / 2 + tn
+      tm_i = (int)((__builtin_sqrtf(8.f * (float)id + 1.f) - 1.f) * 0.5f);
+      while (tm_i * (tm_i + 1) / 2 > id) tm_i--;
+      while ((tm_i + 1) * (tm_i + 2) / 2 <= id) tm_i++;
+      tn_i = id - tm_i * (tm_i + 1) / 2;
+    } else {
+      tm_i = id % p.tiles_m;
+      tn_i = id / p.tiles_m;
+    }
+  }
+  gemm_bf16_tile<BM, BN, AKC, BKC, OutT>(p, tm_i, tn_i, (int)blockIdx.z);
+}
+
+// Several independent weight-gradient products (TN layout, fp32 output) in one launch: the tiles of all products form
+// one sequence of workgroups, so the compute units that run out of tiles of one product start on the next one
+// instead of idling until the slowest tile of a round has finished, and there is one launch instead of one per weight.
+// Each product's first workgroup id is a multiple of 8, which keeps the id -> XCD correspondence that the tile map
+// relies on; the surplus ids do nothing.
+// This pays for short contractions (one micro-batch per product).  For long ones it loses: the 32 tiles an XCD runs at
+// a time share operand panels through its L2 only while they walk the contraction in step, which they do when a
+// launch starts them together and stop doing once tiles of different products and start times are mixed.
+__global__ __launch_bounds__(256) void gemm_tn_grouped_kernel(GroupedTable g) {
+  int lo = 0, hi = g.n - 1;                   // last product whose first workgroup id is <= blockIdx.x
+  const int bid = (int)blockIdx.x;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (g.first_block[mid] <= bid) lo = mid; else hi = mid - 1;
+  }
+  const GroupedProduct& q = g.prod[lo];
+  const int pid = bid - g.first_block[lo];
+  const int tiles_m = (q.M + 255) / 256, tiles_n = (q.N + 255) / 256;
+  if (pid >= tiles_m * tiles_n) return;
+  GemmParams p{};
+  p.A = q.A; p.B = q.B; p.C = q.C;
+  p.lda = q.lda; p.ldb = q.ldb; p.ldc = q.ldc;
+  p.M = q.M; p.N = q.N; p.K = q.K;
+  p.batch_inner = 1; p.tiles_m = tiles_m; p.tiles_n = tiles_n;
+  p.alpha = 1.f; p.accumulate = q.accumulate; p.causal = CAUSAL_NONE;
+  int tm_i, tn_i;
+  tile_of_block(pid, tiles_m, tiles_n, tm_i, tn_i);
+  gemm_bf16_tile<256, 256, false, false, float>(p, tm_i, tn_i, 0);
+}
+
 // ------------------------------------------------------------------------------------------ ceiling
 // Register-resident MFMA loop: 4 waves per compute unit, 16 independent 32x32x16 bf16 MFMAs per iteration on
 // operands that never leave the registers.  It measures what the matrix pipes sustain under the chip's power
@@ -576,6 +611,34 @@ static hipError_t dispatch_layout(int layout, const GemmParams& p, int batch, hi
     case TN: return launch_bf16<BM, BN, false, false, OutT>(p, batch, s);
   }
   return hipErrorInvalidValue;
+}
+
+hipError_t gemm_tn_grouped(const GroupedProduct* prods, int n, hipStream_t s) {
+  constexpr size_t smem = (size_t)STAGES * (256 + 256) * BK * sizeof(bf16_t);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_grouped_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  for (int base = 0; base < n; base += kMaxGrouped) {
+    GroupedTable g{};
+    int blocks = 0;
+    for (int i = base; i < n && g.n < kMaxGrouped; i++) {
+      if (prods[i].M <= 0 || prods[i].N <= 0) continue;
+      g.prod[g.n] = prods[i];
+      g.first_block[g.n] = blocks;
+      const int tiles = ((prods[i].M + 255) / 256) * ((prods[i].N + 255) / 256);
+      blocks += (tiles + 7) & ~7;
+      g.n++;
+    }
+    if (g.n == 0) continue;
+    hipLaunchKernelGGL(gemm_tn_grouped_kernel, dim3((unsigned)blocks), dim3(256), smem, s, g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {

@@ -53,6 +53,23 @@ inline GemmArgs gemm_args(int layout, int M, int N, int K, const void* A, long l
 // dtype: 0 = fp32 storage, 1 = bf16 storage (matches tbp_dtype).
 hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s);
 
+// Several bf16 weight-gradient products C (=, +=) A^T B (TN layout, fp32 C, alpha = 1) run as ONE launch.
+// Same operand rules as the bf16 TN product of gemm(): 16-byte aligned pointers, extents and leading dimensions
+// multiples of 8.
+struct GroupedProduct {
+  const void* A; const void* B; float* C;     // A [K, M] (lda), B [K, N] (ldb), C [M, N] (ldc)
+  int M, N, K;
+  int lda, ldb, ldc;
+  int accumulate;
+};
+constexpr int kMaxGrouped = 40;               // products per launch (the table travels as a kernel argument)
+struct GroupedTable {
+  int n;
+  int first_block[kMaxGrouped];
+  GroupedProduct prod[kMaxGrouped];
+};
+hipError_t gemm_tn_grouped(const GroupedProduct* prods, int n, hipStream_t s);
+
 hipError_t rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, const void* g, void* y, hipStream_t s);
 constexpr int kNormPartialBlocks = 256;     // row-block partials of the gain gradient
 hipError_t rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,

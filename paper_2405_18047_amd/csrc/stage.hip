@@ -360,21 +360,51 @@ tbp_status p2_product(tbp_stage* st, int layer, int xt, int dyt, int mb0, int K,
 tbp_status run_p2(tbp_stage* st, const int* mbs, int n, int mode, int accumulate, hipStream_t s) {
   const Dims& c = st->c;
   struct Prod { int x, dy; float* const* dw; bool attn_only; };
-  for (int l = 0; l < c.L; l++) {
-    const Prod prods[4] = {{W_H1, W_DQKV, st->dw_qkv.data(), true}, {W_A, W_DX1, st->dw_o.data(), true},
-                           {W_H2, W_DGU, st->dw_gu.data(), false}, {W_M, W_DX2, st->dw_d.data(), false}};
-    for (const Prod& p : prods) {
-      if (p.attn_only && !c.attn) continue;
-      if (mode == TBP_P2_KCONCAT) {
-        tbp_status r = p2_product(st, l, p.x, p.dy, mbs[0], n * c.T, p.dw[l], accumulate, s);
-        if (r != TBP_OK) return r;
-      } else {
-        for (int i = 0; i < n; i++) {
-          tbp_status r = p2_product(st, l, p.x, p.dy, mbs[i], c.T, p.dw[l], (accumulate || i > 0) ? 1 : 0, s);
+  auto prods_of = [&](Prod (&out)[4]) {
+    const Prod all[4] = {{W_H1, W_DQKV, st->dw_qkv.data(), true}, {W_A, W_DX1, st->dw_o.data(), true},
+                         {W_H2, W_DGU, st->dw_gu.data(), false}, {W_M, W_DX2, st->dw_d.data(), false}};
+    for (int i = 0; i < 4; i++) out[i] = all[i];
+  };
+  Prod prods[4];
+  prods_of(prods);
+  if (c.dtype == TBP_BF16 && mode == TBP_P2_LOOP) {
+    // bf16, one micro-batch per product: all weight-gradient products of the stage for that micro-batch go into one
+    // grouped launch, each launch accumulating on the previous one.  (The K-concatenated products are long enough
+    // that one launch per weight, which starts its tiles in step, is the faster arrangement.)
+    std::vector<tbp::GroupedProduct> table;
+    for (int i = 0; i < n; i++) {
+      table.clear();
+      const int mb0 = mbs[i];
+      const int K = c.T;
+      for (int l = 0; l < c.L; l++)
+        for (const Prod& p : prods) {
+          if (p.attn_only && !c.attn) continue;
+          tbp::GroupedProduct g{};
+          g.M = (int)w_width(c, p.x); g.N = (int)w_width(c, p.dy); g.K = K;
+          g.A = st->wslab(l, p.x, mb0); g.lda = g.M;
+          g.B = st->wslab(l, p.dy, mb0); g.ldb = g.N;
+          g.C = p.dw[l]; g.ldc = g.N;
+          g.accumulate = (accumulate || i > 0) ? 1 : 0;
+          table.push_back(g);
+        }
+      TBP_HIP(tbp::gemm_tn_grouped(table.data(), (int)table.size(), s));
+    }
+  } else {
+    for (int l = 0; l < c.L; l++)
+      for (const Prod& p : prods) {
+        if (p.attn_only && !c.attn) continue;
+        if (mode == TBP_P2_KCONCAT) {
+          tbp_status r = p2_product(st, l, p.x, p.dy, mbs[0], n * c.T, p.dw[l], accumulate, s);
           if (r != TBP_OK) return r;
+        } else {
+          for (int i = 0; i < n; i++) {
+            tbp_status r = p2_product(st, l, p.x, p.dy, mbs[i], c.T, p.dw[l], (accumulate || i > 0) ? 1 : 0, s);
+            if (r != TBP_OK) return r;
+          }
         }
       }
-    }
+  }
+  for (int l = 0; l < c.L; l++) {
     if (c.attn) TBP_HIP(tbp::gain_grad_sum(st->gain_part(l, 0), mbs, n, c.d, accumulate, st->dg1[l], s));
     TBP_HIP(tbp::gain_grad_sum(st->gain_part(l, 1), mbs, n, c.d, accumulate, st->dg2[l], s));
   }

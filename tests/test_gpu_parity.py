@@ -28,6 +28,8 @@ def _say(msg):
 GEMM_SHAPES = [  # (M, N, K): several tiles plus ragged tails in every dimension (multiples of 8 for bf16)
     (256, 256, 64), (520, 392, 200), (1000, 136, 72), (136, 1000, 328), (264, 520, 1096), (8, 8, 8),
     (4096, 4344, 72), (4344, 4096, 40),     # 272 large tiles: the output is cut into whole rounds + a small-tile rest
+    # long contractions on 192 / 272 large tiles with a ragged last tile in M, N and K (the weight-gradient kernel)
+    (4096, 3064, 264), (3064, 4096, 1000), (4096, 4344, 328),
 ]
 
 
