@@ -96,27 +96,34 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
 // LDS image of one operand tile (R rows/columns of the output x BK of the contraction), laid out so that
 // (a) every 1 KiB piece is what one wave-wide 16-byte-per-lane copy writes (64 consecutive 16-byte granules),
 // (b) the MFMA fragment reads are free of bank conflicts without padding:
-//   KC (contraction index contiguous in memory): image [R][BK], 4 granules per row; granule g of row r sits in
-//       slot g ^ ((r >> 2) & 3): the 16 lanes served per clock (256 bytes) then touch 16 different 16-byte bank groups.
-//       A fragment read is one ds_read_b128 per lane.
+//   KC (contraction index contiguous in memory): image [R][depth], 4 or 8 granules per row; granule g of row r sits
+//       in slot g ^ ((r >> 2) & 3) (depth 32) or g ^ ((r >> 1) & 7) (depth 64): the 16 lanes served per clock (256
+//       bytes) then touch 16 different 16-byte bank groups.  A fragment read is one ds_read_b128 per lane.
 //   KS (contraction index strided in memory): image [BK][R] as in memory, R/8 granules per row; granule
 //       pairs (32 bytes = 16 columns) are swizzled: pair q of row k sits in pair slot q ^ (k & 3).  A fragment
 //       read is two ds_read_b64_tr_b16 (transpose reads), each covering 4 k x 16 columns per 16-lane group:
 //       within a group lane j addresses row k + j/4, columns 4*(j%4)..+3 and receives 4 consecutive k of column j.
-template <int R, bool KC>
+template <int R, bool KC, int KD = BK>
 struct OperandTile {
-  static constexpr int BYTES = R * BK * 2;
+  static constexpr int BYTES = R * KD * 2;
   static constexpr int CHUNKS = BYTES / 1024;       // wave-wide copies per tile
   static constexpr int PER_WAVE = CHUNKS / 4;
   static constexpr int GPR = R / 8;                 // granules per image row (KS)
+  static constexpr int GR = KD / 8;                 // granules per image row (KC): 4 (64-byte rows) or 8 (128-byte rows)
+  static constexpr int RPB = 16 / GR;               // KC rows per 256 bytes (one pass over all banks)
   static_assert(CHUNKS % 4 == 0, "tile must split evenly over 4 waves");
+  static_assert(KD == 32 || KD == 64, "slot depth");
+
+  // KC swizzle: granule g of row r sits in slot g ^ ((r / RPB) % GR), so 16 consecutive rows at one logical granule
+  // cover the 16 bank groups once.
+  static __device__ __forceinline__ int kc_swz(int row) { return (row / RPB) & (GR - 1); }
 
   // Global byte offset (relative to the tile origin) and contraction index covered by lane p of chunk c.
   static __device__ __forceinline__ void copy_plan(int c, int p, long ld, int origin, int extent, unsigned& goff,
                                                    int& kidx) {
     if constexpr (KC) {
-      const int row = 16 * c + (p >> 2);
-      const int g = (p & 3) ^ ((row >> 2) & 3);
+      const int row = (64 / GR) * c + p / GR;
+      const int g = (p % GR) ^ kc_swz(row);
       goff = (origin + row < extent) ? (unsigned)((long)row * ld * 2 + g * 16) : kOob;
       kidx = g * 8;
     } else {
@@ -128,22 +135,23 @@ struct OperandTile {
     }
   }
   // Per-lane byte offset inside the image of the fragment of MFMA tile 0 (rows/columns w0..w0+31), variant v:
-  // KC: v = k-step (0, 1);  KS: v = parity of the MFMA tile index.
+  // KC: v = k-step (0 .. KD/16 - 1);  KS: v = parity of the MFMA tile index.
   static __device__ __forceinline__ int frag_base(int lane, int w0, int v) {
     if constexpr (KC) {
       const int row = w0 + (lane & 31);
       const int g = 2 * v + (lane >> 5);
-      return row * (BK * 2) + ((g ^ ((row >> 2) & 3)) << 4);
+      return row * (KD * 2) + ((g ^ kc_swz(row)) << 4);
     } else {
       const int k = 8 * (lane >> 5) + ((lane & 15) >> 2);
       const int q = w0 / 16 + ((lane >> 4) & 1) + 2 * v;
       return k * (R * 2) + ((q ^ (k & 3)) << 5) + 8 * (lane & 3);
     }
   }
+  static constexpr int VARIANTS = KC ? KD / 16 : 2;
   static __device__ __forceinline__ constexpr int variant(int ks, int t) { return KC ? ks : (t & 1); }
   // Byte offset of (k-step ks, MFMA tile t) relative to frag_base(..., variant(ks, t)).
   static __device__ __forceinline__ constexpr int frag_step(int ks, int t) {
-    return KC ? t * 32 * BK * 2 : ks * 16 * R * 2 + (t >> 1) * 128;
+    return KC ? t * 32 * KD * 2 : ks * 16 * R * 2 + (t >> 1) * 128;
   }
 };
 
@@ -160,12 +168,17 @@ __device__ __forceinline__ bf16x8 read_frag(lds_u8* q) {
 }
 
 // One output tile (tm_i, tn_i) of batch entry z of the product described by p.
-template <int BM, int BN, bool AKC, bool BKC, typename OutT>
+// KD = contraction depth of one LDS slot: 32 with a ring of 4 slots, or 64 with 2 slots.  The deeper slot is for
+// operands whose contraction index is contiguous in memory: their copies then fetch 128 contiguous bytes per tile
+// row, a whole cache line, where the 32-deep slot fetches every line in two halves one iteration apart and doubles
+// the number of requests to the L2.
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD = BK>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, int tn_i, int z) {
+  constexpr int NS = KD == 32 ? STAGES : 2;     // ring slots
   constexpr int WM = BM / 2, WN = BN / 2;       // per-wave tile
   constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wave
-  using TA = OperandTile<BM, AKC>;
-  using TB = OperandTile<BN, BKC>;
+  using TA = OperandTile<BM, AKC, KD>;
+  using TB = OperandTile<BN, BKC, KD>;
   constexpr int STAGE_BYTES = TA::BYTES + TB::BYTES;
   constexpr int NA = TA::PER_WAVE, NB = TB::PER_WAVE;
   constexpr int L = NA + NB;                    // asynchronous copies per thread per slot
@@ -189,7 +202,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   } else if (p.causal == CAUSAL_K_BEGIN) {
     k_lo = m0;
   }
-  const int nk = (k_hi - k_lo + BK - 1) / BK;
+  const int nk = (k_hi - k_lo + KD - 1) / KD;
 
   const int zo = z / p.batch_inner, zi = z - zo * p.batch_inner;
   const bf16_t* A = reinterpret_cast<const bf16_t*>(p.A) + zo * p.sAo + zi * p.sAi;
@@ -214,7 +227,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   // Running state of the copy stream (all wave-uniform): next tile's operand addresses, ring slot and remaining k.
   uint64_t a_next = reinterpret_cast<uint64_t>(Ablk + (long)k_lo * a_kstep);
   uint64_t b_next = reinterpret_cast<uint64_t>(Bblk + (long)k_lo * b_kstep);
-  const uint64_t a_adv = (uint64_t)(BK * a_kstep * 2), b_adv = (uint64_t)(BK * b_kstep * 2);
+  const uint64_t a_adv = (uint64_t)(KD * a_kstep * 2), b_adv = (uint64_t)(KD * b_kstep * 2);
   int slot_next = 0, krem_next = k_hi - k_lo;
   auto next_job = [&]() {
     CopyJob j;
@@ -224,8 +237,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
     j.sb = j.sa + TA::BYTES;
     j.krem = krem_next;
     a_next += a_adv; b_next += b_adv;
-    slot_next = (slot_next + 1 == STAGES) ? 0 : slot_next + 1;
-    krem_next -= BK;
+    slot_next = (slot_next + 1 == NS) ? 0 : slot_next + 1;
+    krem_next -= KD;
     return j;
   };
   auto copy_one = [&](const CopyJob& j, int c) {     // c-th of this wave's L copies of the job
@@ -233,12 +246,11 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
     else dma16(j.sb + (c - NA) * 4096, j.dB, b_kidx[c - NA] < j.krem ? b_goff[c - NA] : kOob);
   };
 
-  int a_base[2], b_base[2];
+  int a_base[TA::VARIANTS], b_base[TB::VARIANTS];
 #pragma unroll
-  for (int v = 0; v < 2; v++) {
-    a_base[v] = TA::frag_base(lane, wm * WM, v);
-    b_base[v] = TB::frag_base(lane, wn * WN, v) + TA::BYTES;
-  }
+  for (int v = 0; v < TA::VARIANTS; v++) a_base[v] = TA::frag_base(lane, wm * WM, v);
+#pragma unroll
+  for (int v = 0; v < TB::VARIANTS; v++) b_base[v] = TB::frag_base(lane, wn * WN, v) + TA::BYTES;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -263,8 +275,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   // Fragment fetch order = order of first use by the MFMA sequence (i-major): a0, then every b, then a1, a2, ...;
   // one fetch per MFMA from the start of the region, so the fragments the NEXT region needs first have the whole
   // region to arrive and the last fetches still have MM - UNITS MFMAs of cover.  The copies fill the second half.
-  auto region = [&](const bf16x8* fa, const bf16x8* fb, bf16x8* na, bf16x8* nb, int nt, int nks, const CopyJob* job) {
-    lds_u8* const st = lds + (nt % STAGES) * STAGE_BYTES;
+  auto region = [&](const bf16x8* fa, const bf16x8* fb, bf16x8* na, bf16x8* nb, lds_u8* st, int nks, const CopyJob* job) {
 #pragma unroll
     for (int m = 0; m < MM; m++) {
       const int i = m / TN, j = m % TN;
@@ -287,33 +298,64 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  static_assert(BK == 32 && STAGES >= 3, "the pipeline is written for two k-steps per slot");
-  if (nk > 0) {
+  static_assert(BK == 32 && STAGES >= 3, "the 32-deep pipeline is written for two k-steps per slot");
+  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  auto first_fragments = [&]() {
 #pragma unroll
-    for (int t = 0; t < STAGES - 1; t++) {
-      const CopyJob j = next_job();
+    for (int i = 0; i < TM; i++) fa0[i] = read_frag<BM, AKC>(lds + a_base[TA::variant(0, i)] + TA::frag_step(0, i));
 #pragma unroll
-      for (int c = 0; c < L; c++) copy_one(j, c);
+    for (int j = 0; j < TN; j++) fb0[j] = read_frag<BN, BKC>(lds + b_base[TB::variant(0, j)] + TB::frag_step(0, j));
+  };
+  if constexpr (KD == 32) {
+    if (nk > 0) {
+#pragma unroll
+      for (int t = 0; t < STAGES - 1; t++) {
+        const CopyJob j = next_job();
+#pragma unroll
+        for (int c = 0; c < L; c++) copy_one(j, c);
+      }
+      wait_vmem<(STAGES - 2) * L>();          // tile 0 has landed (this wave's share)
+      __syncthreads();
+      first_fragments();
+      for (int t = 0; t < nk; t++) {
+        region(fa0, fb0, fa1, fb1, lds + (t % STAGES) * STAGE_BYTES, 1, nullptr);
+        wait_vmem<(STAGES - 3) * L>();        // tile t+1 has landed (this wave's share)
+        __syncthreads();                      // everyone's share of t+1 landed; everyone is done with tile t-1
+        const CopyJob j = next_job();         // tile t + STAGES - 1
+        __builtin_amdgcn_sched_barrier(0);
+        region(fa1, fb1, fa0, fb0, lds + ((t + 1) % STAGES) * STAGE_BYTES, 0, &j);
+      }
+      wait_vmem<0>();                         // drain the (empty) copies issued past the end
     }
-    wait_vmem<(STAGES - 2) * L>();          // tile 0 has landed (this wave's share)
-    __syncthreads();
-    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-    {
-      lds_u8* const st = lds;
+  } else {
+    // 64-deep slots, two of them: four k-steps per iteration.  The barrier sits before the last k-step: by then every
+    // wave has fetched its last fragments of slot t (they are multiplied from registers in the last k-step), so the
+    // barrier both publishes slot t+1 and frees slot t, whose refill with tile t+2 is issued during that last
+    // k-step and has a whole iteration to land.
+    if (nk > 0) {
 #pragma unroll
-      for (int i = 0; i < TM; i++) fa0[i] = read_frag<BM, AKC>(st + a_base[TA::variant(0, i)] + TA::frag_step(0, i));
+      for (int t = 0; t < 2; t++) {
+        const CopyJob j = next_job();
 #pragma unroll
-      for (int j = 0; j < TN; j++) fb0[j] = read_frag<BN, BKC>(st + b_base[TB::variant(0, j)] + TB::frag_step(0, j));
+        for (int c = 0; c < L; c++) copy_one(j, c);
+      }
+      wait_vmem<L>();
+      __syncthreads();
+      first_fragments();
+      for (int t = 0; t < nk; t++) {
+        lds_u8* const cur = lds + (t & 1) * STAGE_BYTES;
+        lds_u8* const nxt = lds + ((t + 1) & 1) * STAGE_BYTES;
+        region(fa0, fb0, fa1, fb1, cur, 1, nullptr);
+        region(fa1, fb1, fa0, fb0, cur, 2, nullptr);
+        region(fa0, fb0, fa1, fb1, cur, 3, nullptr);
+        wait_vmem<0>();                       // tile t+1 has landed (this wave's share)
+        __syncthreads();
+        const CopyJob j = next_job();         // tile t + 2 into the slot of tile t
+        __builtin_amdgcn_sched_barrier(0);
+        region(fa1, fb1, fa0, fb0, nxt, 0, &j);
+      }
+      wait_vmem<0>();
     }
-    for (int t = 0; t < nk; t++) {
-      region(fa0, fb0, fa1, fb1, t, 1, nullptr);
-      wait_vmem<(STAGES - 3) * L>();        // tile t+1 has landed (this wave's share)
-      __syncthreads();                      // everyone's share of t+1 landed; everyone is done with tile t-1
-      const CopyJob j = next_job();         // tile t + STAGES - 1
-      __builtin_amdgcn_sched_barrier(0);
-      region(fa1, fb1, fa0, fb0, t + 1, 0, &j);
-    }
-    wait_vmem<0>();                         // drain the (empty) copies issued past the end
   }
 
   // ---- epilogue.  Accumulator element e of a 32x32 tile sits at row 8*(e/4) + 4*(lane/32) + e%4, column lane%32:
@@ -327,7 +369,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   constexpr int SW = WN + 4;                // strip row stride in floats
   typedef LDS_AS float lds_f32;
   lds_f32* const strip = reinterpret_cast<lds_f32*>(lds + wave * (32 * SW * 4));
-  static_assert(4 * 32 * SW * 4 <= STAGES * STAGE_BYTES, "strips must fit in the ring");
+  static_assert(4 * 32 * SW * 4 <= NS * STAGE_BYTES, "strips must fit in the ring");
   constexpr int V = sizeof(OutT) == 4 ? 4 : 8;          // elements per 16-byte store
   constexpr int LPR = WN / V, RPI = 64 / LPR;           // lanes per strip row, rows per wave-wide store
   const int sr = lane / LPR, sc = (lane % LPR) * V;
@@ -404,7 +446,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   }
 }
 
-template <int BM, int BN, bool AKC, bool BKC, typename OutT>
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   int tm_i, tn_i;
   if (gridDim.z == 1) {
@@ -426,7 +468,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
       tn_i = id / p.tiles_m;
     }
   }
-  gemm_bf16_tile<BM, BN, AKC, BKC, OutT>(p, tm_i, tn_i, (int)blockIdx.z);
+  gemm_bf16_tile<BM, BN, AKC, BKC, OutT, KD>(p, tm_i, tn_i, (int)blockIdx.z);
 }
 
 // Several independent weight-gradient products (TN layout, fp32 output) in one launch: the tiles of all products form
@@ -580,14 +622,14 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
 }
 
 // ------------------------------------------------------------------------------------------ host
-template <int BM, int BN, bool AKC, bool BKC, typename OutT>
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD>
 static hipError_t launch_bf16(const GemmParams& p0, int batch, hipStream_t s) {
   GemmParams p = p0;
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N + BN - 1) / BN;
-  constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
+  constexpr size_t smem = (size_t)(KD == 32 ? STAGES : 2) * (BM + BN) * KD * sizeof(bf16_t);
   static_assert(smem <= 160 * 1024, "LDS budget of one gfx950 compute unit");
-  auto kern = gemm_bf16_kernel<BM, BN, AKC, BKC, OutT>;
+  auto kern = gemm_bf16_kernel<BM, BN, AKC, BKC, OutT, KD>;
   static bool attr_set = false;     // once per instantiation; harmless if two threads race
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -603,12 +645,19 @@ static hipError_t launch_bf16(const GemmParams& p0, int batch, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Slot depth by layout and tile size: operands with a contiguous contraction index get the 64-deep slots on the
+// large tiles (whole cache lines per tile row: up to 8 % faster); on the small tiles, which run two or three
+// workgroups per compute unit and overlap that way, the 4-slot ring of 32-deep slots stays ahead.
+#ifndef TBP_KC_DEPTH_SMALL
+#define TBP_KC_DEPTH_SMALL 32
+#endif
 template <int BM, int BN, typename OutT>
 static hipError_t dispatch_layout(int layout, const GemmParams& p, int batch, hipStream_t s) {
+  constexpr int KD = BM >= 256 ? 64 : TBP_KC_DEPTH_SMALL;
   switch (layout) {
-    case NN: return launch_bf16<BM, BN, true, false, OutT>(p, batch, s);
-    case NT: return launch_bf16<BM, BN, true, true, OutT>(p, batch, s);
-    case TN: return launch_bf16<BM, BN, false, false, OutT>(p, batch, s);
+    case NN: return launch_bf16<BM, BN, true, false, OutT, KD>(p, batch, s);
+    case NT: return launch_bf16<BM, BN, true, true, OutT, KD>(p, batch, s);
+    case TN: return launch_bf16<BM, BN, false, false, OutT, 32>(p, batch, s);
   }
   return hipErrorInvalidValue;
 }
