@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--no-kernel-rates", action="store_true")
     ap.add_argument("--no-loop-compare", action="store_true",
                     help="skip the extra loop-mode p2 steps (profiles: every dW launch is then a K-concatenated one)")
+    ap.add_argument("--no-call-orders", action="store_true",
+                    help="skip the extra passes that time other call orders (p2 interleaved with p1, partial flushes)")
     ap.add_argument("--probe", action="store_true",
                     help="for hardware-counter runs: one forward/p1 pass, then a plain 1 GiB device copy (calibration) "
                          "and two K-concatenated p2 passes; prints nothing but a marker line")
@@ -179,6 +181,8 @@ def main() -> int:
             t = json.load(fh).get(shape.name)
         if t:
             out["roofline"]["traffic"] = t["hbm_bytes_per_launch"]
+    if not args.no_call_orders:
+        out["call_orders"] = call_orders(st, tbp, torch, xs, dys, x_out, dx_out, M, statistics.median(p1_ms))
     if not args.no_kernel_rates:
         out["p1_elementwise_gbps"] = kernel_rates(shape, tbp, torch, dev, tdt)
     st.close()
@@ -187,6 +191,100 @@ def main() -> int:
         out["cpu_baseline"] = cpu_baseline(shape)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def call_orders(st, tbp, torch, xs, dys, x_out, dx_out, M, p1_deferred_ms) -> dict:
+    """Other orders of the same calls on the same stash (outside the timed steps; every pass starts from a reset
+    stage and forwards all micro-batches first, then times backward-p1 and backward-p2 together):
+      deferred                 p1 of every micro-batch, then one K-concatenated p2 (the timed steps' order)
+      interleaved              p1(m) then p2({m}) for each m on one stream (what a plain autograd backward does)
+      interleaved_two_streams  p2({m}) goes to a second stream as soon as p1(m) is done and overlaps p1(m+1)
+      flush_every_k            K-concatenated p2 over k micro-batches after every k-th p1: the bound on how many
+                               micro-batches of derivatives are held at once (the memory-saving variant)"""
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()              # default priority
+    res = {}
+
+    def run(name, body, reps=2):
+        best = None
+        for _ in range(reps):
+            st.reset()
+            for m in range(M):
+                st.forward(m, xs[m], x_out)
+            torch.cuda.synchronize()
+            peak[0] = peak[1] = 0
+            a, b = ev(), ev()
+            a.record()
+            p1_events = body()
+            main.wait_stream(side)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b)
+            if best is None or ms < best["p1_plus_p2_ms"]:
+                best = {"p1_plus_p2_ms": round(ms, 3)}
+                if p1_events:
+                    lat = [x.elapsed_time(y) for x, y in p1_events]
+                    best["p1_ms_per_microbatch"] = round(statistics.median(lat), 3)
+                    best["p1_inflation"] = round(statistics.median(lat) / p1_deferred_ms, 3)
+                best["peak_derivative_stash_bytes"] = peak[0]      # output derivatives held for p2, at their maximum
+        res[name] = best
+
+    peak = [0, 0]                              # [peak bytes of derivatives held for p2, micro-batches holding them]
+
+    def timed_p1(m):
+        x, y = ev(), ev()
+        before = st.stats()["w_live_bytes"]
+        x.record(); st.backward_p1(m, dys[m], dx_out); y.record()
+        peak[1] += 1
+        peak[0] = max(peak[0], peak[1] * (st.stats()["w_live_bytes"] - before))
+        return (x, y)
+
+    def p2(mbs, mode, accumulate):
+        st.backward_p2(mbs, mode, accumulate=accumulate)
+        peak[1] -= len(mbs)
+
+    def deferred():
+        e = [timed_p1(m) for m in range(M)]
+        p2(list(range(M)), tbp.TBP_P2_KCONCAT, False)
+        return e
+
+    def interleaved():
+        e = []
+        for m in range(M):
+            e.append(timed_p1(m))
+            p2([m], tbp.TBP_P2_LOOP, m > 0)
+        return e
+
+    def two_streams():
+        e = []
+        for m in range(M):
+            e.append(timed_p1(m))
+            side.wait_stream(main)
+            with torch.cuda.stream(side):
+                p2([m], tbp.TBP_P2_LOOP, m > 0)
+        return e
+
+    def flush_every(k):
+        def body():
+            e = []
+            for m in range(M):
+                e.append(timed_p1(m))
+                if (m + 1) % k == 0 or m == M - 1:
+                    first = (m // k) * k
+                    p2(list(range(first, m + 1)), tbp.TBP_P2_KCONCAT, first > 0)
+            return e
+        return body
+
+    run("deferred", deferred)
+    run("interleaved", interleaved)
+    run("interleaved_two_streams", two_streams)
+    k = 1
+    while k < M:
+        k *= 2
+        if k < M:
+            run(f"flush_every_{k}", flush_every(k))
+    return res
 
 
 def kernel_rates(shape, tbp, torch, dev, tdt) -> dict:

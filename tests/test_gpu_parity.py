@@ -216,6 +216,33 @@ def test_stage_matches_oracle(name, mode):
     st.close()
 
 
+def test_p2_on_a_second_stream_overlapping_the_next_p1():
+    """p2({m}) enqueued on a second stream once p1(m) is done, while p1(m+1) runs on the first: the weight-gradient
+    products read only what p1(m) has finished writing, so the gradients equal the oracle's."""
+    shape = SMALL["tiles_bf16"].replace(n_microbatches=3)
+    params, xs, dys = _stage_inputs(shape)
+    _, dxs, grads = run_oracle(shape, params, xs, dys)
+    tol = stage_tolerance(shape.dtype)
+    st = make_gpu_stage(shape, params)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    for m in range(3):
+        st.forward(m, to_dev(xs[m], shape.dtype))
+    g_dxs = []
+    for m in range(3):
+        g_dxs.append(st.backward_p1(m, to_dev(dys[m], shape.dtype)))
+        side.wait_stream(main)
+        with torch.cuda.stream(side):
+            st.backward_p2([m], tbp.TBP_P2_LOOP, accumulate=(m > 0))
+    main.wait_stream(side)
+    torch.cuda.synchronize()
+    for k, v in st.grads.items():
+        for l in range(len(v)):
+            assert max_rel(to_np(v[l]), grads[k][l]) < tol, (k, l)
+    for m in range(3):
+        assert max_rel(to_np(g_dxs[m]), dxs[m]) < tol
+    st.close()
+
+
 def test_p2_call_patterns_agree():
     """p2 right after each p1 (ordinary backprop), p2 by subsets, loop and K-concatenated: same gradients."""
     shape = SMALL["small_bf16"].replace(n_microbatches=4)
