@@ -184,7 +184,16 @@ def main() -> int:
     if not args.no_call_orders:
         out["call_orders"] = call_orders(st, tbp, torch, xs, dys, x_out, dx_out, M, statistics.median(p1_ms))
     if not args.no_kernel_rates:
-        out["p1_elementwise_gbps"] = kernel_rates(shape, tbp, torch, dev, tdt)
+        rates = kernel_rates(shape, tbp, torch, dev, tdt)
+        out["p1_elementwise_gbps"] = rates
+        # fractions of what this machine sustains (register-resident MFMA loop, plain device copy), beside the nominal ones
+        loop_ref = rates["mfma_loop_reference"]["TFLOP/s"]
+        copy_ref = rates["device_copy_reference"]["GB/s"]
+        out["roofline"]["mfma_loop_tflops"] = loop_ref
+        out["roofline"]["frac_of_mfma_loop"] = round(p2_tflops / loop_ref, 4)
+        for k, v in rates.items():
+            if "us" in v:
+                v["frac_of_device_copy"] = round(v["GB/s"] / copy_ref, 4)
     st.close()
     del st
     if not args.no_cpu_baseline:

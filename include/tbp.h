@@ -145,7 +145,10 @@ tbp_status tbp_stage_reset(tbp_stage* st);
 /* C[M,N] (= or +=) alpha * op(A) op(B) (+ R).  layout: 0 = NN (A [M,K], B [K,N]), 1 = NT (A [M,K],
  * B [N,K]: dX = dY W^T, Section 3.1), 2 = TN (A [K,M], B [K,N]: dW = X^T dY, Section 3.1).
  * out_f32 != 0: C is fp32 (and may accumulate); else C has the storage type and R (optional,
- * same shape and leading dimension as C) is added before rounding. */
+ * same shape and leading dimension as C) is added before rounding.
+ * bf16 storage: A, B, C and R must be 16-byte aligned; the contiguous extent of A and of B, N, lda, ldb and
+ * ldc must be multiples of 8 (every lane moves 16 bytes); TBP_EINVAL otherwise.  fp32 storage has no such rule.
+ * K == 0 writes zeros (or leaves an accumulated C alone); M == 0 or N == 0 does nothing. */
 tbp_status tbp_gemm(int dtype, int layout, int M, int N, int K, float alpha, const void* A, int lda,
                     const void* B, int ldb, void* C, int ldc, int out_f32, int accumulate, const void* R,
                     void* stream);
