@@ -174,6 +174,24 @@ tbp_status tbp_rope(int dtype, int rows, int seq, int n_heads, int head_dim, int
 tbp_status tbp_softmax_fwd(int dtype, int n_mat, int seq, int causal, const float* scores, void* P, void* stream);
 tbp_status tbp_softmax_p1(int dtype, int n_mat, int seq, int causal, const void* P, void* dP_dS, void* stream);
 
+/* Fused scaled-dot-product attention per (sequence, head) (an operation with no backward-p2 and a significant
+ * backward-p1, Section 4.1), bf16 storage, head_dim 64 or 128.  qkv: device [batch*seq, ld_qkv], column blocks
+ * q | k | v of n_heads*head_dim each (q and k already rotated); out: device [batch*seq, ld_out], heads concatenated;
+ * lse: device [batch, n_heads, seq] fp32 = log2 of the row's sum of exp2(score * log2(e) / sqrt(head_dim)), all that
+ * backward-p1 needs to rebuild the probabilities.  causal != 0: query i sees keys j <= i.  Pointers 16-byte aligned,
+ * leading dimensions multiples of 8.  Neither scores nor probabilities are written to memory. */
+tbp_status tbp_attention_fwd(int dtype, int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv,
+                             int ld_qkv, void* out, int ld_out, float* lse, void* stream);
+
+/* Backward-p1 of the fused attention: dq, dk, dv (not yet rotated back) into the q | k | v column blocks of dqkv
+ * [batch*seq, ld_dqkv], from qkv, the forward's out and lse, and d_out = derivative of out (out and d_out dense:
+ * ld_out == n_heads*head_dim).  The probabilities are rebuilt from lse; dS = P * (dP - rowsum(d_out * out)).
+ * scratch: device, 256-byte aligned, >= tbp_attention_p1_scratch_bytes(batch, n_heads, seq) (row sums and dS^T). */
+size_t tbp_attention_p1_scratch_bytes(int batch, int n_heads, int seq);
+tbp_status tbp_attention_p1(int dtype, int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv,
+                            int ld_qkv, const void* out, const void* d_out, int ld_out, const float* lse, void* dqkv,
+                            int ld_dqkv, void* scratch, void* stream);
+
 /* Measurement aid (no paper passage: it prices the hardware, not the method): a register-resident loop of
  * 32x32x16 bf16 MFMAs, blocks x 4 wavefronts x iters x 16 instructions = blocks*iters*2^21 FLOP, touching no memory
  * inside the loop.  What it sustains is the practical ceiling of the matrix pipes under the chip's power management.

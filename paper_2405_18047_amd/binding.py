@@ -14,6 +14,7 @@ __all__ = [
     "TBP_F32", "TBP_BF16", "TBP_P2_LOOP", "TBP_P2_KCONCAT", "NN", "NT", "TN", "TbpError", "lib", "library_path",
     "tbp_config", "tbp_stash_query", "Stage", "tbp_gemm", "tbp_rmsnorm_fwd", "tbp_rmsnorm_p1", "tbp_swiglu_fwd",
     "tbp_swiglu_p1", "tbp_rope_table", "tbp_rope", "tbp_softmax_fwd", "tbp_softmax_p1", "tbp_version",
+    "tbp_attention_fwd", "tbp_attention_p1",
     "config_from_shape",
 ]
 
@@ -89,6 +90,10 @@ def lib() -> C.CDLL:
         L.tbp_stage_stash_stats.argtypes = [C.c_void_p, C.POINTER(_tbp_stash_stats)]
         L.tbp_stage_reset.argtypes = [C.c_void_p]
         L.tbp_mfma_ceiling.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tbp_attention_p1_scratch_bytes.argtypes = [C.c_int] * 3
+        L.tbp_attention_p1_scratch_bytes.restype = C.c_size_t
+        L.tbp_attention_p1.argtypes = [C.c_int] * 6 + [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        L.tbp_attention_fwd.argtypes = [C.c_int] * 6 + [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.tbp_rmsnorm_p1_scratch_bytes.argtypes = [C.c_int]
         L.tbp_rope_table_bytes.argtypes = [C.c_int, C.c_int]
         _lib = L
@@ -286,6 +291,31 @@ def tbp_softmax_fwd(scores, causal, dtype):
     _check(lib().tbp_softmax_fwd(TBP_BF16 if dtype == torch.bfloat16 else TBP_F32, n_mat, seq, 1 if causal else 0,
                                  _ptr(scores), _ptr(P), _stream()))
     return P
+
+
+def tbp_attention_fwd(qkv, seq, n_heads, head_dim, causal=True):
+    """qkv [batch*seq, 3*n_heads*head_dim] (q | k | v, rotated) -> (out [batch*seq, n_heads*head_dim], lse2 [batch, heads, seq])."""
+    rows = qkv.shape[0]
+    batch = rows // seq
+    out = torch.empty((rows, n_heads * head_dim), dtype=qkv.dtype, device=qkv.device)
+    lse = torch.empty((batch, n_heads, seq), dtype=torch.float32, device=qkv.device)
+    _check(lib().tbp_attention_fwd(_dt(qkv), batch, n_heads, seq, head_dim, 1 if causal else 0, _ptr(qkv), qkv.stride(0),
+                                   _ptr(out), out.stride(0), _ptr(lse), _stream()))
+    return out, lse
+
+
+def tbp_attention_p1(qkv, out, d_out, lse, seq, n_heads, head_dim, causal=True):
+    """-> dqkv [batch*seq, 3*n_heads*head_dim] (dq | dk | dv, not rotated back)."""
+    rows = qkv.shape[0]
+    batch = rows // seq
+    dqkv = torch.empty_like(qkv)
+    nbytes = lib().tbp_attention_p1_scratch_bytes(batch, n_heads, seq)
+    scratch = torch.empty(nbytes + 256, dtype=torch.uint8, device=qkv.device)
+    base = (scratch.data_ptr() + 255) // 256 * 256
+    _check(lib().tbp_attention_p1(_dt(qkv), batch, n_heads, seq, head_dim, 1 if causal else 0, _ptr(qkv), qkv.stride(0),
+                                  _ptr(out), _ptr(d_out), out.stride(0), _ptr(lse), _ptr(dqkv), dqkv.stride(0), base,
+                                  _stream()))
+    return dqkv
 
 
 def tbp_softmax_p1(P, dP, causal):

@@ -1,0 +1,478 @@
+// Fused scaled-dot-product attention for gfx950 (bf16 storage, fp32 accumulation, head_dim 64 or 128): the forward
+// keeps neither scores nor probabilities, only the log-sum-exp of every row; backward-p1 recomputes the
+// probabilities from it.  Attention is one of the operations with no backward-p2 and a significant backward-p1
+// (Section 4.1), so everything here is on the critical path of the pipeline.
+//
+// Orientation.  With the 32x32x16 MFMA an accumulator lane owns ONE column and 16 rows of a 32x32 tile.  The
+// kernels arrange every product so that the softmax row statistics belong to the lane's column:
+//   forward, dQ pass   S^T = K Q^T   (column = query): row max / row sum of a query are a reduction over the lane's own
+//                      registers plus one exchange with lane ^ 32; the running rescale of the output is a per-lane
+//                      scalar;
+//   dK/dV pass         S   = Q K^T   (column = key), the statistics come from memory (one value per register row).
+// In both cases the probabilities (and score gradients) leave the accumulators straight into the B operand of the next
+// product: B lane (column c, half g) wants 8 contraction indices, and accumulator registers 8u .. 8u+7 of the
+// lane are rows 16u + {0..3, 8..11} + 4g of its column, so k-step u of the next product simply DEFINES its
+// contraction order to be that row order and the A operand is fetched in the same order (transpose reads of four
+// consecutive rows at 16u + 4g and at 16u + 8 + 4g).  No shuffles, no LDS round trip for P.
+#include "kernels.h"
+#include "gfx950.h"
+
+namespace tbp {
+
+struct AttnParams {
+  const bf16_t* qkv; long ld_qkv;      // [B*S, >= 3*H*DH]: q | k | v column blocks of H*DH each
+  bf16_t* out; long ld_out;            // [B*S, >= H*DH]
+  float* lse;                          // [B, H, S]: log2 of the row's sum of exp2(score * scale * log2 e)
+  int B, H, S, causal;
+  float scale_log2e;
+};
+
+// LDS image of `rows` x DH bf16, filled by asynchronous copies (a wave-wide copy writes 1 KiB = 4 or 8 rows).
+// The 16-byte granule G of row r sits in slot G ^ swz(r).  swz is a bit permutation of the row index chosen so that
+// both access patterns are free of bank conflicts: 16 consecutive rows at one granule (row fragments, ds_read_b128)
+// and 4 consecutive rows x 2 adjacent granules (transpose fragments, ds_read_b64_tr_b16).
+template <int DH>
+struct HeadTile {
+  static constexpr int RB = DH * 2, GPRW = DH / 8, RPC = 1024 / RB;
+  static __device__ __forceinline__ int swz(int r) {
+    if constexpr (DH == 128) return ((r & 3) << 1) | ((r >> 2) & 1) | (r & 8);
+    else return (((r >> 1) & 1) << 1) | ((r >> 2) & 1) | (((r >> 3) & 1) << 2);
+  }
+  static __device__ __forceinline__ int at(int r, int G) { return r * RB + ((G ^ swz(r)) << 4); }
+  // Copy plan of lane p of chunk c: tile row and byte offset inside the source row block.
+  static __device__ __forceinline__ void plan(int c, int p, long ld, int& row, unsigned& goff) {
+    row = RPC * c + p / GPRW;
+    const int G = (p % GPRW) ^ swz(row);
+    goff = (unsigned)((long)row * ld * 2 + G * 16);
+  }
+  // A-operand fragment of MFMA rows r0 .. r0+31 of the image, contraction = columns 16 s .. 16 s + 15.
+  static __device__ __forceinline__ bf16x8 rows_frag(lds_u8* img, int r0, int s, int lane) {
+    return *reinterpret_cast<LDS_AS const bf16x8*>(img + at(r0 + (lane & 31), 2 * s + (lane >> 5)));
+  }
+  // A-operand fragment of the TRANSPOSED image: MFMA rows = columns 32 t .. 32 t + 31, contraction = image rows
+  // r0 + 16 u + {0..3, 8..11} + 4 (lane / 32)  (the accumulator row order, see the file header).
+  static __device__ __forceinline__ bf16x8 cols_frag(lds_u8* img, int r0, int u, int t, int lane) {
+    const int i = lane & 15, q = (lane >> 4) & 1, g = lane >> 5;
+    const int r = r0 + 16 * u + 4 * g + (i >> 2);
+    const int G = 2 * (2 * t + q) + ((i & 3) >> 1);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s16x4*>(img + at(r, G) + 8 * (i & 1)));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s16x4*>(img + at(r + 8, G) + 8 * (i & 1)));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  }
+};
+
+__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& c, int u) {
+  bf16x8 b;
+#pragma unroll
+  for (int t = 0; t < 8; t++) b[t] = (bf16_t)c[8 * u + t];
+  return b;
+}
+
+// ------------------------------------------------------------------------------------------ forward
+// One workgroup = 4 waves x 32 queries of one (sequence, head); keys and values stream through LDS in blocks of 64,
+// double-buffered.  Per block and wave: S^T (64 keys x 32 queries), online softmax per lane, O^T += V^T P^T.
+template <int DH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(AttnParams p) {
+  using HT = HeadTile<DH>;
+  constexpr int KS = DH / 16, DT = DH / 32, BKV = 64;
+  constexpr int IMG = BKV * HT::RB, SLOT = 2 * IMG;
+  constexpr int NCH = IMG / 1024 / 4;                 // copies per wave per operand per block
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  lds_u8* const lds = LDS_PTR(unsigned char, smem_raw);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+
+  const int lane = threadIdx.x & 63, ql = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // workgroup ids run over (head, sequence) fastest and query blocks slowest, longest (last) query blocks first: with
+  // causal masking the work of a block grows with its index, and the blocks still to start near the end are short ones
+  const int qb = (int)gridDim.y - 1 - (int)blockIdx.y;
+  const int h = (int)blockIdx.x % p.H, b = (int)blockIdx.x / p.H;
+  const int q0 = qb * 128, qw0 = q0 + 32 * wave, query = qw0 + ql;
+  const int d = p.H * DH;
+  const long tok0 = (long)b * p.S;
+
+  // ---- this lane's query row as B operand of S^T = K Q^T: 8 consecutive head-dim values per k-step
+  bf16x8 qf[KS];
+  {
+    const __amdgpu_buffer_rsrc_t dq = make_rsrc(p.qkv + tok0 * p.ld_qkv + h * DH, (uint32_t)((long)p.S * p.ld_qkv * 2));
+    const unsigned off = query < p.S ? (unsigned)(((long)query * p.ld_qkv + 8 * g) * 2) : kOob;
+#pragma unroll
+    for (int s = 0; s < KS; s++)
+      qf[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(dq, off, 32 * s, 0));
+  }
+
+  // ---- copy plan of this wave: chunks wave, wave + 4, ... of the K image and of the V image
+  int c_row[NCH];
+  unsigned c_off[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; i++) HT::plan(wave + 4 * i, lane, p.ld_qkv, c_row[i], c_off[i]);
+  const int kv_end = p.causal ? (q0 + 128 < p.S ? q0 + 128 : p.S) : p.S;
+  const int nblk = (kv_end + BKV - 1) / BKV;
+  auto issue = [&](int j) {
+    const int kv0 = j * BKV;
+    const bf16_t* kb = p.qkv + (tok0 + kv0) * p.ld_qkv + d + h * DH;
+    const uint32_t bytes = (uint32_t)((long)(p.S - kv0) * p.ld_qkv * 2);     // rows of this sequence only
+    const u32x4 dk = make_desc(kb, bytes), dv = make_desc(kb + d, bytes);
+    const uint32_t base = lds0 + (j & 1) * SLOT + wave * 1024;
+#pragma unroll
+    for (int i = 0; i < NCH; i++) {
+      const unsigned off = (kv0 + c_row[i] < p.S) ? c_off[i] : kOob;
+      dma16(base + i * 4096, dk, off);
+      dma16(base + IMG + i * 4096, dv, off);
+    }
+  };
+
+  f32x16 ot[DT];
+#pragma unroll
+  for (int t = 0; t < DT; t++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) ot[t][e] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  issue(0);
+  for (int j = 0; j < nblk; j++) {
+    wait_vmem<0>();
+    __syncthreads();                   // block j has landed; every wave is done with the other slot
+    if (j + 1 < nblk) issue(j + 1);
+    const int kv0 = j * BKV;
+    if (p.causal && kv0 > qw0 + 31) continue;          // every key of the block is after every query of this wave
+    lds_u8* const kimg = lds + (j & 1) * SLOT;
+    lds_u8* const vimg = kimg + IMG;
+    // S^T for the two key tiles of the block as two interleaved accumulation chains (consecutive MFMAs are
+    // independent), fragments fetched one k-step ahead
+    f32x16 st[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) st[kt][e] = 0.f;
+    {
+      bf16x8 k0 = HT::rows_frag(kimg, 0, 0, lane), k1 = HT::rows_frag(kimg, 32, 0, lane);
+#pragma unroll
+      for (int s = 0; s < KS; s++) {
+        bf16x8 n0 = k0, n1 = k1;
+        if (s + 1 < KS) { n0 = HT::rows_frag(kimg, 0, s + 1, lane); n1 = HT::rows_frag(kimg, 32, s + 1, lane); }
+        st[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[s], st[0], 0, 0, 0);
+        st[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[s], st[1], 0, 0, 0);
+        k0 = n0; k1 = n1;
+      }
+    }
+    // keys beyond the query (causal) or beyond the sequence do not take part (blocks on the diagonal / at the end only)
+    if ((p.causal && kv0 + BKV - 1 > qw0) || kv0 + BKV > p.S) {
+      const int last = p.causal ? (query < p.S - 1 ? query : p.S - 1) : p.S - 1;      // last key this lane's query sees
+      const int rel = last - kv0 - 4 * g;
+#pragma unroll
+      for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+        for (int e = 0; e < 16; e++)
+          st[kt][e] = (32 * kt + 8 * (e >> 2) + (e & 3) > rel) ? -INFINITY : st[kt][e];
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) mx = fmaxf(mx, st[kt][e]);
+    mx = fmaxf(mx, xor32(mx)) * p.scale_log2e;          // scale > 0: the maximum commutes with it
+    const float mnew = fmaxf(m, mx);
+    if (__any(mnew != m)) {                           // some query's maximum moved: rescale what is accumulated
+      const float alpha = __builtin_amdgcn_exp2f(m - mnew);    // first block: exp2(-inf) = 0
+      l *= alpha;
+#pragma unroll
+      for (int t = 0; t < DT; t++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) ot[t][e] *= alpha;
+      m = mnew;
+    }
+    float rs = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        const float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][e], p.scale_log2e, -m));
+        st[kt][e] = pe;
+        rs += pe;
+      }
+    l += rs + xor32(rs);
+    // O^T += V^T P^T: 4 (kt, u) steps x DT independent accumulators, fragments one step ahead
+    bf16x8 vf[DT];
+#pragma unroll
+    for (int t = 0; t < DT; t++) vf[t] = HT::cols_frag(vimg, 0, 0, t, lane);
+#pragma unroll
+    for (int ku = 0; ku < 4; ku++) {
+      const bf16x8 pb = pack8(st[ku >> 1], ku & 1);
+      bf16x8 nf[DT];
+#pragma unroll
+      for (int t = 0; t < DT; t++) nf[t] = ku < 3 ? HT::cols_frag(vimg, 32 * ((ku + 1) >> 1), (ku + 1) & 1, t, lane) : vf[t];
+#pragma unroll
+      for (int t = 0; t < DT; t++) ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t], pb, ot[t], 0, 0, 0);
+#pragma unroll
+      for (int t = 0; t < DT; t++) vf[t] = nf[t];
+    }
+  }
+
+  // ---- o = O^T / l, transposed back on the way out: a lane holds 4 consecutive head-dim values per register group
+  if (query < p.S) {
+    const float inv = 1.f / l;
+    bf16_t* orow = p.out + (tok0 + query) * p.ld_out + h * DH;
+#pragma unroll
+    for (int t = 0; t < DT; t++)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; e4++) {
+        bf16x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; r++) v[r] = (bf16_t)(ot[t][4 * e4 + r] * inv);
+        *reinterpret_cast<bf16x4*>(orow + 32 * t + 8 * e4 + 4 * g) = v;
+      }
+    if (g == 0) p.lse[((long)b * p.H + h) * p.S + query] = m + __builtin_amdgcn_logf(l);
+  }
+}
+
+// ------------------------------------------------------------------------------------------ backward-p1: dK, dV, dS^T
+// One workgroup = 4 waves x 32 keys of one (sequence, head); queries, their output derivatives and their row
+// statistics stream through LDS in steps of 64 queries, double-buffered.  Per 32 queries and wave:
+//   S = Q K^T and dP = dO V^T (column = key; K and V rows of the lane's key stay in registers as B operands),
+//   P = exp2(S c - lse), dS = P (dP - delta), then dV^T += dO^T P and dK^T += Q^T dS with P and dS fed from the
+//   accumulators (see the file header).  dS^T is also written out ([key][query], storage type): dQ = dS K is a
+//   contraction over keys, which this kernel splits over workgroups, and is left to a batched product.
+struct AttnBwdParams {
+  const bf16_t* qkv; long ld_qkv;
+  const bf16_t* dout; long ld_do;      // [B*S, >= H*DH] derivative of the attention output
+  const float* lse;                    // [B, H, S] from the forward
+  const float* delta;                  // [B*S, H]: rowsum(dout * out) per (token, head)
+  bf16_t* dqkv; long ld_dqkv;          // dk and dv blocks are written (columns H*DH.. and 2*H*DH..)
+  bf16_t* dst;                         // [B, H, S(key), S(query)] = dS^T
+  int B, H, S, causal;
+  float scale, scale_log2e;
+};
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_kv_kernel(AttnBwdParams p) {
+  using HT = HeadTile<DH>;
+  constexpr int KS = DH / 16, DT = DH / 32, BQ = 64;
+  constexpr int IMG = BQ * HT::RB, SLOT = 2 * IMG + 1024;     // Q image, dO image, 64 x (lse, delta)
+  constexpr int NCH = IMG / 1024 / 4;
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  lds_u8* const lds = LDS_PTR(unsigned char, smem_raw);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+
+  const int tid = threadIdx.x, lane = tid & 63, kl = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kb = blockIdx.y;                                  // key blocks in order: with causal masking the first are the longest
+  const int h = (int)blockIdx.x % p.H, b = (int)blockIdx.x / p.H;
+  const int kv0 = kb * 128, kw0 = kv0 + 32 * wave, key = kw0 + kl;
+  const int d = p.H * DH;
+  const long tok0 = (long)b * p.S;
+  const long bh = (long)b * p.H + h;
+
+  // ---- the lane's key row and value row as B operands (8 consecutive head-dim values per k-step)
+  bf16x8 kfb[KS], vfb[KS];
+  {
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.qkv + tok0 * p.ld_qkv + d + h * DH, (uint32_t)((long)p.S * p.ld_qkv * 2));
+    const unsigned off = key < p.S ? (unsigned)(((long)key * p.ld_qkv + 8 * g) * 2) : kOob;
+#pragma unroll
+    for (int s = 0; s < KS; s++) {
+      kfb[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, 32 * s, 0));
+      vfb[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, 32 * s + 2 * d, 0));
+    }
+  }
+
+  int c_row[NCH];
+  unsigned cq_off[NCH], cd_off[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; i++) {
+    HT::plan(wave + 4 * i, lane, p.ld_qkv, c_row[i], cq_off[i]);
+    HT::plan(wave + 4 * i, lane, p.ld_do, c_row[i], cd_off[i]);
+  }
+  const int step0 = p.causal ? kv0 / BQ : 0;                  // queries before the first key of the block see none of it
+  const int nstep = (p.S + BQ - 1) / BQ;
+  typedef LDS_AS float lds_f32;
+  auto issue = [&](int i) {
+    const int q0 = i * BQ;
+    const uint32_t slot = lds0 + ((i - step0) & 1) * SLOT;
+    const u32x4 dq = make_desc(p.qkv + (tok0 + q0) * p.ld_qkv + h * DH, (uint32_t)((long)(p.S - q0) * p.ld_qkv * 2));
+    const u32x4 dd = make_desc(p.dout + (tok0 + q0) * p.ld_do + h * DH, (uint32_t)((long)(p.S - q0) * p.ld_do * 2));
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      const bool ok = q0 + c_row[c] < p.S;
+      dma16(slot + wave * 1024 + c * 4096, dq, ok ? cq_off[c] : kOob);
+      dma16(slot + IMG + wave * 1024 + c * 4096, dd, ok ? cd_off[c] : kOob);
+    }
+    if (tid < 2 * BQ) {                                       // row statistics of the step: lse[0..63], delta[0..63]
+      const int r = tid & (BQ - 1), q = q0 + r;
+      float v = 0.f;
+      if (q < p.S) v = tid < BQ ? p.lse[bh * p.S + q] : p.delta[(tok0 + q) * p.H + h];
+      reinterpret_cast<lds_f32*>(lds + ((i - step0) & 1) * SLOT + 2 * IMG)[tid] = v;
+    }
+  };
+
+  f32x16 dvt[DT], dkt[DT];
+#pragma unroll
+  for (int t = 0; t < DT; t++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) { dvt[t][e] = 0.f; dkt[t][e] = 0.f; }
+
+  bf16_t* const dst_row = p.dst + (bh * p.S + key) * p.S;     // dS^T row of the lane's key
+  if (step0 < nstep) issue(step0);
+  for (int i = step0; i < nstep; i++) {
+    wait_vmem<0>();
+    __syncthreads();
+    if (i + 1 < nstep) issue(i + 1);
+    lds_u8* const qimg = lds + ((i - step0) & 1) * SLOT;
+    lds_u8* const dimg = qimg + IMG;
+    const lds_f32* const stat = reinterpret_cast<const lds_f32*>(qimg + 2 * IMG);
+#pragma unroll
+    for (int qt = 0; qt < 2; qt++) {
+      const int qt0 = i * BQ + 32 * qt;                         // first query of the tile
+      if (qt0 >= p.S) continue;
+      if (p.causal && qt0 + 31 < kw0) {                         // every query of the tile is before every key of this wave:
+        if (key < p.S) {                                        // the tile of dS^T is zero
+#pragma unroll
+          for (int e4 = 0; e4 < 4; e4++) {
+            const int q = qt0 + 8 * e4 + 4 * g;
+            if (q < p.S) *reinterpret_cast<u32x2*>(dst_row + q) = u32x2{0u, 0u};
+          }
+        }
+        continue;
+      }
+      f32x16 sa, da;
+#pragma unroll
+      for (int e = 0; e < 16; e++) { sa[e] = 0.f; da[e] = 0.f; }
+      {
+        bf16x8 fq = HT::rows_frag(qimg, 32 * qt, 0, lane), fd = HT::rows_frag(dimg, 32 * qt, 0, lane);
+#pragma unroll
+        for (int s = 0; s < KS; s++) {
+          bf16x8 nq = fq, nd = fd;
+          if (s + 1 < KS) { nq = HT::rows_frag(qimg, 32 * qt, s + 1, lane); nd = HT::rows_frag(dimg, 32 * qt, s + 1, lane); }
+          sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq, kfb[s], sa, 0, 0, 0);
+          da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd, vfb[s], da, 0, 0, 0);
+          fq = nq; fd = nd;
+        }
+      }
+      // P and dS in place: register e is query qt0 + 8 (e / 4) + 4 g + e % 4, statistics fetched four rows at a time
+      const bool diag = p.causal && qt0 < kw0 + 31;             // some (query, key) pairs of the tile are masked
+#pragma unroll
+      for (int e4 = 0; e4 < 4; e4++) {
+        const f32x4 ls = *reinterpret_cast<const LDS_AS f32x4*>(stat + 32 * qt + 8 * e4 + 4 * g);
+        const f32x4 dl = *reinterpret_cast<const LDS_AS f32x4*>(stat + BQ + 32 * qt + 8 * e4 + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          const int e = 4 * e4 + r;
+          float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sa[e], p.scale_log2e, -ls[r]));
+          if (diag && key > qt0 + 8 * e4 + 4 * g + r) pe = 0.f;
+          sa[e] = pe;
+          da[e] = pe * (da[e] - dl[r]);
+        }
+      }
+      // dS^T out: four consecutive queries of the lane's key row per register group
+      if (key < p.S) {
+#pragma unroll
+        for (int e4 = 0; e4 < 4; e4++) {
+          const int q = qt0 + 8 * e4 + 4 * g;
+          bf16x4 v;
+#pragma unroll
+          for (int r = 0; r < 4; r++) v[r] = (bf16_t)da[4 * e4 + r];
+          if (q < p.S) *reinterpret_cast<bf16x4*>(dst_row + q) = v;
+        }
+      }
+      // dV^T += dO^T P, dK^T += Q^T dS
+#pragma unroll
+      for (int u = 0; u < 2; u++) {
+        const bf16x8 pb = pack8(sa, u), sb = pack8(da, u);
+#pragma unroll
+        for (int t = 0; t < DT; t++) {
+          dvt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HT::cols_frag(dimg, 32 * qt, u, t, lane), pb, dvt[t], 0, 0, 0);
+          dkt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HT::cols_frag(qimg, 32 * qt, u, t, lane), sb, dkt[t], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- dk = scale * dK^T transposed, dv = dV^T transposed: 4 consecutive head-dim values per register group
+  if (key < p.S) {
+    bf16_t* row = p.dqkv + (tok0 + key) * p.ld_dqkv + d + h * DH;
+#pragma unroll
+    for (int t = 0; t < DT; t++)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; e4++) {
+        bf16x4 vk, vv;
+#pragma unroll
+        for (int r = 0; r < 4; r++) { vk[r] = (bf16_t)(dkt[t][4 * e4 + r] * p.scale); vv[r] = (bf16_t)dvt[t][4 * e4 + r]; }
+        *reinterpret_cast<bf16x4*>(row + 32 * t + 8 * e4 + 4 * g) = vk;
+        *reinterpret_cast<bf16x4*>(row + d + 32 * t + 8 * e4 + 4 * g) = vv;
+      }
+  }
+}
+
+template <int DH>
+static hipError_t launch_fwd(const AttnParams& p, hipStream_t s) {
+  constexpr size_t smem = 2 * 2 * 64 * DH * 2;
+  auto kern = attn_fwd_kernel<DH>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)(p.H * p.B), (unsigned)((p.S + 127) / 128)), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
+hipError_t attention_fwd(int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv, long ld_qkv,
+                         void* out, long ld_out, float* lse, hipStream_t s) {
+  if (batch <= 0 || n_heads <= 0 || seq <= 0) return hipSuccess;
+  AttnParams p{};
+  p.qkv = (const bf16_t*)qkv; p.ld_qkv = ld_qkv; p.out = (bf16_t*)out; p.ld_out = ld_out; p.lse = lse;
+  p.B = batch; p.H = n_heads; p.S = seq; p.causal = causal;
+  p.scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
+  if (head_dim == 128) return launch_fwd<128>(p, s);
+  if (head_dim == 64) return launch_fwd<64>(p, s);
+  return hipErrorInvalidValue;
+}
+
+template <int DH>
+static hipError_t launch_bwd_kv(const AttnBwdParams& p, hipStream_t s) {
+  constexpr size_t smem = 2 * (2 * 64 * DH * 2 + 1024);
+  auto kern = attn_bwd_kv_kernel<DH>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)(p.H * p.B), (unsigned)((p.S + 127) / 128)), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
+hipError_t attention_p1(int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv, long ld_qkv,
+                        const void* out, const void* d_out, long ld_out, const float* lse, void* dqkv, long ld_dqkv,
+                        float* delta, void* ds_t, hipStream_t s) {
+  if (batch <= 0 || n_heads <= 0 || seq <= 0) return hipSuccess;
+  if (ld_out != (long)n_heads * head_dim) return hipErrorInvalidValue;      // the row-dot kernel takes dense rows
+  hipError_t e = head_rowdot(1, batch * seq, n_heads, head_dim, d_out, out, delta, s);
+  if (e != hipSuccess) return e;
+  AttnBwdParams p{};
+  p.qkv = (const bf16_t*)qkv; p.ld_qkv = ld_qkv; p.dout = (const bf16_t*)d_out; p.ld_do = ld_out;
+  p.lse = lse; p.delta = delta; p.dqkv = (bf16_t*)dqkv; p.ld_dqkv = ld_dqkv; p.dst = (bf16_t*)ds_t;
+  p.B = batch; p.H = n_heads; p.S = seq; p.causal = causal;
+  p.scale = 1.f / sqrtf((float)head_dim);
+  p.scale_log2e = 1.4426950408889634f * p.scale;
+  if (head_dim == 128) e = launch_bwd_kv<128>(p, s);
+  else if (head_dim == 64) e = launch_bwd_kv<64>(p, s);
+  else return hipErrorInvalidValue;
+  if (e != hipSuccess) return e;
+  // dq = scale * dS k = scale * (dS^T)^T k per (sequence, head): contraction over keys, causal: keys <= query
+  const long d = (long)n_heads * head_dim;
+  GemmArgs g = gemm_args(TN, seq, head_dim, seq, ds_t, seq, (const char*)qkv + d * 2, ld_qkv, dqkv, ld_dqkv);
+  g.alpha = p.scale;
+  g.batch = batch * n_heads; g.batch_inner = n_heads;
+  g.sAo = (long)n_heads * seq * seq; g.sAi = (long)seq * seq;
+  g.sBo = (long)seq * ld_qkv; g.sBi = head_dim;
+  g.sCo = (long)seq * ld_dqkv; g.sCi = head_dim;
+  g.causal = causal ? CAUSAL_K_END : CAUSAL_NONE;
+  return gemm(1, g, s);
+}
+
+}  // namespace tbp

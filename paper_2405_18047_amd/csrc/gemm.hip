@@ -13,19 +13,9 @@
 //   which handles ragged M, N and K without branches.
 // fp32 path: plain FMA tile kernel with generic strides (the fp32 configuration is tiny).
 #include "kernels.h"
+#include "gfx950.h"
 
 namespace tbp {
-
-typedef __bf16 bf16_t;
-typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
-#define LDS_AS __attribute__((address_space(3)))
 
 struct GemmParams {
   const void* A; const void* B; void* C; const void* R;
@@ -46,33 +36,7 @@ struct GemmParams {
 
 constexpr int BK = 32;                     // contraction depth of one LDS slot
 constexpr int STAGES = 4;                  // LDS ring: one slot being multiplied, three in flight
-constexpr unsigned kOob = 0x80000000u;     // byte offset beyond every descriptor: the copy delivers zero
 
-typedef LDS_AS unsigned char lds_u8;
-
-// Buffer descriptor of a 2 GiB window starting at p, held in scalar registers (readfirstlane makes the
-// workgroup-uniform address provably uniform for the compiler).
-__device__ __forceinline__ u32x4 make_desc(const void* p) {
-  const uint64_t a = reinterpret_cast<uint64_t>(p);
-  u32x4 d;
-  d[0] = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)a);
-  d[1] = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
-  d[2] = 0x7fffffffu;
-  d[3] = 0x00020000u;
-  return d;
-}
-
-// Asynchronous global -> LDS copy of 16 bytes per lane: lane i's data lands at lds_base + 16*i (lds_base is
-// wave-uniform and goes through M0).  The copy is tracked by the vector-memory counter only; it is written as
-// inline assembly so that the compiler's wait insertion does not drain the whole ring before every LDS read.
-__device__ __forceinline__ void dma16(uint32_t lds_base, u32x4 desc, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-               :: "s"(lds_base), "v"(voff), "s"(desc) : "memory");
-}
-
-template <int N> __device__ __forceinline__ void wait_vmem() {   // at most N vector-memory operations outstanding
-  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
-}
 
 // Workgroup id -> (tile row, tile column).  Workgroups are handed to the 8 XCDs round-robin; the first
 // step makes each XCD own a contiguous range of the tile sequence (so its private L2 sees neighbouring

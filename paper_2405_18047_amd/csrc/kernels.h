@@ -89,6 +89,19 @@ hipError_t head_rowdot(int dtype, int rows, int n_heads, int head_dim, const voi
 hipError_t gain_grad_sum(const float* parts, const int* rows_host, int n, int d, int accumulate, float* out,
                          hipStream_t s);
 
+// Fused attention (bf16 storage only, head_dim 64 or 128).  qkv: [batch*seq, ld_qkv] with column blocks q | k | v of
+// n_heads*head_dim each (q and k already rotated); out: [batch*seq, ld_out]; lse: [batch, n_heads, seq] fp32, the log2
+// of each row's sum of exp2(score / sqrt(head_dim) * log2 e).
+hipError_t attention_fwd(int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv, long ld_qkv,
+                         void* out, long ld_out, float* lse, hipStream_t s);
+
+// Backward-p1 of the same: dq, dk, dv into the column blocks of dqkv from qkv, the forward's output and lse and the
+// output derivative d_out (dense rows: ld_out == n_heads*head_dim).  delta: scratch [batch*seq, n_heads] fp32;
+// ds_t: scratch [batch, n_heads, seq, seq] storage type (receives dS^T).
+hipError_t attention_p1(int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv, long ld_qkv,
+                        const void* out, const void* d_out, long ld_out, const float* lse, void* dqkv, long ld_dqkv,
+                        float* delta, void* ds_t, hipStream_t s);
+
 // Register-resident MFMA loop (measurement aid): blocks x 4 waves x iters x 16 MFMAs of 32x32x16.
 // seed: 8 x 64 x 8 bf16 values; sink: blocks * 256 floats.
 hipError_t mfma_ceiling(int blocks, int iters, const void* seed, float* sink, hipStream_t s);

@@ -584,6 +584,50 @@ tbp_status tbp_gemm(int dtype, int layout, int M, int N, int K, float alpha, con
   return TBP_OK;
 }
 
+tbp_status tbp_attention_fwd(int dtype, int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv,
+                             int ld_qkv, void* out, int ld_out, float* lse, void* stream) {
+  if (dtype != TBP_BF16) return fail(TBP_EINVAL, "fused attention is built for bf16 storage only");
+  if (head_dim != 64 && head_dim != 128) return fail(TBP_EINVAL, "fused attention needs head_dim 64 or 128");
+  if (batch < 0 || n_heads < 0 || seq < 0) return fail(TBP_EINVAL, "negative size");
+  if (batch == 0 || n_heads == 0 || seq == 0) return TBP_OK;
+  if (!qkv || !out || !lse) return fail(TBP_EINVAL, "qkv, out and lse must be non-null");
+  if (ld_qkv < 3 * n_heads * head_dim || ld_out < n_heads * head_dim || ld_qkv % 8 || ld_out % 8)
+    return fail(TBP_EINVAL, "leading dimensions must cover the head columns and be multiples of 8");
+  if ((uintptr_t)qkv % 16 || (uintptr_t)out % 16) return fail(TBP_EINVAL, "qkv and out must be 16-byte aligned");
+  if (seq % 8) return fail(TBP_EINVAL, "seq must be a multiple of 8");
+  if (seq > tbp::kMaxSeq) return fail(TBP_EINVAL, "seq %d above the limit %d", seq, tbp::kMaxSeq);
+  TBP_HIP(tbp::attention_fwd(batch, n_heads, seq, head_dim, causal ? 1 : 0, qkv, ld_qkv, out, ld_out, lse,
+                             static_cast<hipStream_t>(stream)));
+  return TBP_OK;
+}
+
+size_t tbp_attention_p1_scratch_bytes(int batch, int n_heads, int seq) {
+  if (batch <= 0 || n_heads <= 0 || seq <= 0) return 0;
+  return align_up((size_t)batch * seq * n_heads * sizeof(float), 256) + (size_t)batch * n_heads * seq * seq * 2;
+}
+
+tbp_status tbp_attention_p1(int dtype, int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv,
+                            int ld_qkv, const void* out, const void* d_out, int ld_out, const float* lse, void* dqkv,
+                            int ld_dqkv, void* scratch, void* stream) {
+  if (dtype != TBP_BF16) return fail(TBP_EINVAL, "fused attention is built for bf16 storage only");
+  if (head_dim != 64 && head_dim != 128) return fail(TBP_EINVAL, "fused attention needs head_dim 64 or 128");
+  if (batch < 0 || n_heads < 0 || seq < 0) return fail(TBP_EINVAL, "negative size");
+  if (batch == 0 || n_heads == 0 || seq == 0) return TBP_OK;
+  if (!qkv || !out || !d_out || !lse || !dqkv || !scratch) return fail(TBP_EINVAL, "null pointer");
+  const int d = n_heads * head_dim;
+  if (ld_qkv < 3 * d || ld_dqkv < 3 * d || ld_qkv % 8 || ld_dqkv % 8) return fail(TBP_EINVAL, "leading dimensions must cover 3*n_heads*head_dim and be multiples of 8");
+  if (ld_out != d) return fail(TBP_EINVAL, "out and d_out must be dense [batch*seq, n_heads*head_dim]");
+  if (seq % 8) return fail(TBP_EINVAL, "seq must be a multiple of 8");
+  if (seq > tbp::kMaxSeq) return fail(TBP_EINVAL, "seq %d above the limit %d", seq, tbp::kMaxSeq);
+  if ((uintptr_t)qkv % 16 || (uintptr_t)out % 16 || (uintptr_t)d_out % 16 || (uintptr_t)dqkv % 16 || (uintptr_t)scratch % 256)
+    return fail(TBP_EINVAL, "tensors must be 16-byte aligned, scratch 256-byte aligned");
+  float* delta = static_cast<float*>(scratch);
+  void* ds_t = static_cast<char*>(scratch) + align_up((size_t)batch * seq * n_heads * sizeof(float), 256);
+  TBP_HIP(tbp::attention_p1(batch, n_heads, seq, head_dim, causal ? 1 : 0, qkv, ld_qkv, out, d_out, ld_out, lse, dqkv,
+                            ld_dqkv, delta, ds_t, static_cast<hipStream_t>(stream)));
+  return TBP_OK;
+}
+
 tbp_status tbp_mfma_ceiling(int blocks, int iters, const void* seed, float* sink, void* stream) {
   if (blocks < 1 || blocks > 65536 || iters < 0 || !seed || !sink) return fail(TBP_EINVAL, "bad mfma ceiling arguments");
   TBP_HIP(tbp::mfma_ceiling(blocks, iters, seed, sink, static_cast<hipStream_t>(stream)));

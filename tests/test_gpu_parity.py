@@ -171,7 +171,48 @@ def test_softmax_fwd_and_p1(dtype, n_mat, seq, causal):
         assert max_rel(dS, ds_ref) < tol
 
 
+@pytest.mark.parametrize("seq,nb,H,dh,causal", [(256, 1, 2, 128, True), (136, 2, 3, 64, True), (520, 1, 2, 128, True),
+                                                (200, 1, 2, 64, False), (1024, 1, 4, 128, True), (8, 1, 1, 64, True)])
+def test_fused_attention_backward(seq, nb, H, dh, causal):
+    """dq, dk, dv of the fused backward (probabilities rebuilt from the row log-sum-exp) against the oracle's."""
+    _say(f"attention p1 seq={seq} batch={nb} heads={H} dh={dh} causal={causal}")
+    d = H * dh
+    q, k, v, do = (_rnd(42, n, (nb * seq, d), "bf16") for n in ("q", "k", "v", "do"))
+    q64, k64, v64 = q.astype(np.float64), k.astype(np.float64), v.astype(np.float64)
+    _, P = ops.attention_fwd(q64, k64, v64, seq, H, dh, causal)
+    dq, dk, dv = ops.attention_p1(do.astype(np.float64), q64, k64, v64, P, seq, H, dh)
+    qkv = to_dev(np.concatenate([q, k, v], axis=1), "bf16")
+    out, lse2 = tbp.tbp_attention_fwd(qkv, seq, H, dh, causal)
+    got = to_np(tbp.tbp_attention_p1(qkv, out, to_dev(do, "bf16"), lse2, seq, H, dh, causal))
+    for name, ref, blk in (("dq", dq, got[:, :d]), ("dk", dk, got[:, d:2 * d]), ("dv", dv, got[:, 2 * d:])):
+        err = max_rel(blk, ref)
+        _say(f"   {name}: {err:.2e}")
+        assert err < 1.5e-2, name
+
+
 # ------------------------------------------------------------------------------------------- whole stage
+@pytest.mark.parametrize("seq,nb,H,dh,causal", [(256, 1, 2, 128, True), (136, 2, 3, 64, True), (520, 1, 2, 128, True),
+                                                (200, 1, 2, 64, False), (1024, 1, 4, 128, True), (8, 1, 1, 64, True)])
+def test_fused_attention_forward(seq, nb, H, dh, causal):
+    """Fused attention against the oracle's materialised form; the row log-sum-exp against what the oracle's
+    probabilities imply (lse_i = s_ii - log P_ii on the diagonal, which is never masked)."""
+    _say(f"attention fwd seq={seq} batch={nb} heads={H} dh={dh} causal={causal}")
+    d = H * dh
+    q, k, v = (_rnd(41, n, (nb * seq, d), "bf16") for n in ("q", "k", "v"))
+    o_ref, P = ops.attention_fwd(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), seq, H, dh, causal)
+    qkv = to_dev(np.concatenate([q, k, v], axis=1), "bf16")
+    out, lse2 = tbp.tbp_attention_fwd(qkv, seq, H, dh, causal)
+    assert max_rel(to_np(out), o_ref) < 1e-2
+    got = to_np(lse2) * np.log(2.0)
+    for b in range(nb):
+        for h in range(H):
+            qh = q[b * seq:(b + 1) * seq, h * dh:(h + 1) * dh].astype(np.float64)
+            kh = k[b * seq:(b + 1) * seq, h * dh:(h + 1) * dh].astype(np.float64)
+            sii = np.sum(qh * kh, axis=1) / np.sqrt(dh)
+            ref = sii - np.log(np.diagonal(P[b, h]))
+            assert np.max(np.abs(got[b, h] - ref)) < 2e-3 * max(1.0, np.max(np.abs(ref)))
+
+
 def _stage_inputs(shape):
     params = si.stage_params(shape)
     xs = [si.stage_input(shape, m) for m in range(shape.n_microbatches)]
