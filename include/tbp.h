@@ -59,6 +59,15 @@ typedef enum { TBP_F32 = 0, TBP_BF16 = 1 } tbp_dtype;
  *            must therefore be ascending consecutive indices (TBP_EINVAL otherwise). */
 typedef enum { TBP_P2_LOOP = 0, TBP_P2_KCONCAT = 1 } tbp_p2_mode;
 
+/* Attention is a functional operation: no backward-p2, everything it keeps is released in backward-p1 (Section 4.2).
+ *   MATERIALISED  scores -> softmax -> P v as separate products; the probabilities P [batch, heads, seq, seq] are
+ *                 stashed from forward to p1 (any dtype, any head_dim);
+ *   FUSED         one forward kernel and one backward kernel that never write scores or probabilities: only the
+ *                 row log-sum-exp [batch, heads, seq] is stashed and p1 rebuilds the probabilities from it
+ *                 (bf16 storage, head_dim 64 or 128; TBP_EINVAL otherwise);
+ *   AUTO          FUSED where it is available, MATERIALISED elsewhere. */
+typedef enum { TBP_ATTN_AUTO = 0, TBP_ATTN_MATERIALISED = 1, TBP_ATTN_FUSED = 2 } tbp_attention;
+
 typedef struct {
   int32_t n_layers;
   int32_t d_model;
@@ -74,6 +83,7 @@ typedef struct {
   int32_t dtype;            /* tbp_dtype */
   float rms_eps;            /* added to the mean square inside the square root */
   float rope_base;
+  int32_t attention;        /* tbp_attention: how the attention of each layer is computed and what it stashes */
 } tbp_config;
 
 /* Per-layer arrays (host arrays of length n_layers holding DEVICE pointers).  The w_* / g* arrays hold

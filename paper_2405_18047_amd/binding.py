@@ -11,7 +11,7 @@ import os
 import torch
 
 __all__ = [
-    "TBP_F32", "TBP_BF16", "TBP_P2_LOOP", "TBP_P2_KCONCAT", "NN", "NT", "TN", "TbpError", "lib", "library_path",
+    "TBP_F32", "TBP_BF16", "TBP_P2_LOOP", "TBP_P2_KCONCAT", "TBP_ATTN_AUTO", "TBP_ATTN_MATERIALISED", "TBP_ATTN_FUSED", "NN", "NT", "TN", "TbpError", "lib", "library_path",
     "tbp_config", "tbp_stash_query", "Stage", "tbp_gemm", "tbp_rmsnorm_fwd", "tbp_rmsnorm_p1", "tbp_swiglu_fwd",
     "tbp_swiglu_p1", "tbp_rope_table", "tbp_rope", "tbp_softmax_fwd", "tbp_softmax_p1", "tbp_version",
     "tbp_attention_fwd", "tbp_attention_p1",
@@ -20,6 +20,7 @@ __all__ = [
 
 TBP_F32, TBP_BF16 = 0, 1
 TBP_P2_LOOP, TBP_P2_KCONCAT = 0, 1
+TBP_ATTN_AUTO, TBP_ATTN_MATERIALISED, TBP_ATTN_FUSED = 0, 1, 2
 NN, NT, TN = 0, 1, 2
 _STATUS = {0: "TBP_OK", 1: "TBP_EINVAL", 2: "TBP_ESTATE", 3: "TBP_ENOMEM", 4: "TBP_EDEVICE"}
 
@@ -33,7 +34,7 @@ class TbpError(RuntimeError):
 class tbp_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "seq", "micro_batch",
                                         "max_microbatches", "act_slots", "causal", "dtype")] + \
-               [("rms_eps", C.c_float), ("rope_base", C.c_float)]
+               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("attention", C.c_int32)]
 
 
 class _tbp_params(C.Structure):
@@ -125,13 +126,14 @@ def _ptr(t):
     return None if (t is None or t.numel() == 0) else C.c_void_p(t.data_ptr())
 
 
-def config_from_shape(shape, act_slots: int = 0, max_microbatches: int | None = None) -> tbp_config:
+def config_from_shape(shape, act_slots: int = 0, max_microbatches: int | None = None,
+                      attention: int = TBP_ATTN_AUTO) -> tbp_config:
     """tbp_config for a seeded_inputs.StageShape-like object (any object with the same field names)."""
     return tbp_config(n_layers=shape.n_layers, d_model=shape.d_model, n_heads=shape.n_heads, head_dim=shape.head_dim,
                       d_ffn=shape.d_ffn, seq=shape.seq, micro_batch=shape.micro_batch,
                       max_microbatches=max_microbatches or shape.n_microbatches, act_slots=act_slots,
                       causal=1 if shape.causal else 0, dtype=TBP_BF16 if shape.dtype == "bf16" else TBP_F32,
-                      rms_eps=shape.rms_eps, rope_base=shape.rope_base)
+                      rms_eps=shape.rms_eps, rope_base=shape.rope_base, attention=attention)
 
 
 def tbp_stash_query(cfg: tbp_config) -> dict:

@@ -45,18 +45,33 @@ struct HeadTile {
     const int G = (p % GPRW) ^ swz(row);
     goff = (unsigned)((long)row * ld * 2 + G * 16);
   }
-  // A-operand fragment of MFMA rows r0 .. r0+31 of the image, contraction = columns 16 s .. 16 s + 15.
-  static __device__ __forceinline__ bf16x8 rows_frag(lds_u8* img, int r0, int s, int lane) {
-    return *reinterpret_cast<LDS_AS const bf16x8*>(img + at(r0 + (lane & 31), 2 * s + (lane >> 5)));
-  }
-  // A-operand fragment of the TRANSPOSED image: MFMA rows = columns 32 t .. 32 t + 31, contraction = image rows
-  // r0 + 16 u + {0..3, 8..11} + 4 (lane / 32)  (the accumulator row order, see the file header).
-  static __device__ __forceinline__ bf16x8 cols_frag(lds_u8* img, int r0, int u, int t, int lane) {
+  // Per-lane byte offsets of the fragment reads, computed once per kernel (the swizzle makes them non-affine in the
+  // k-step, so they are kept in registers; everything else - image, 32-row block, k-step pair - is an immediate).
+  //   rows[s]: A-operand fragment of MFMA rows 0..31 of the image, contraction = columns 16 s .. 16 s + 15.
+  //   cols[t][0/1]: A-operand fragment of the TRANSPOSED image: MFMA rows = columns 32 t .. 32 t + 31, contraction =
+  //            image rows 16 u + {0..3} + 4 (lane / 32) (first read) and 16 u + 8 + {0..3} + 4 (lane / 32) (second):
+  //            the accumulator row order, see the file header.  16 u rows further is an immediate too.
+  struct Offsets { int rows[DH / 16]; int cols[DH / 32][2]; };
+  static __device__ __forceinline__ Offsets offsets(int lane) {
+    Offsets o;
+#pragma unroll
+    for (int s = 0; s < DH / 16; s++) o.rows[s] = at(lane & 31, 2 * s + (lane >> 5));
     const int i = lane & 15, q = (lane >> 4) & 1, g = lane >> 5;
-    const int r = r0 + 16 * u + 4 * g + (i >> 2);
-    const int G = 2 * (2 * t + q) + ((i & 3) >> 1);
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s16x4*>(img + at(r, G) + 8 * (i & 1)));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s16x4*>(img + at(r + 8, G) + 8 * (i & 1)));
+    const int r = 4 * g + (i >> 2);
+#pragma unroll
+    for (int t = 0; t < DH / 32; t++) {
+      const int G = 2 * (2 * t + q) + ((i & 3) >> 1);
+      o.cols[t][0] = at(r, G) + 8 * (i & 1);
+      o.cols[t][1] = at(r + 8, G) + 8 * (i & 1);
+    }
+    return o;
+  }
+  static __device__ __forceinline__ bf16x8 rows_frag(lds_u8* img, const Offsets& o, int r0, int s) {   // r0 % 16 == 0
+    return *reinterpret_cast<LDS_AS const bf16x8*>(img + o.rows[s] + r0 * RB);
+  }
+  static __device__ __forceinline__ bf16x8 cols_frag(lds_u8* img, const Offsets& o, int r0, int u, int t) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s16x4*>(img + o.cols[t][0] + (r0 + 16 * u) * RB));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s16x4*>(img + o.cols[t][1] + (r0 + 16 * u) * RB));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   }
 };
@@ -103,7 +118,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int s = 0; s < KS; s++)
       qf[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(dq, off, 32 * s, 0));
   }
+  // complete here: the compiler's own wait for these registers would otherwise sit inside the loop and, the counter
+  // being in order, also wait for the asynchronous copies issued after them
+  wait_vmem<0>();
 
+  const typename HT::Offsets fo = HT::offsets(lane);
   // ---- copy plan of this wave: chunks wave, wave + 4, ... of the K image and of the V image
   int c_row[NCH];
   unsigned c_off[NCH];
@@ -149,11 +168,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int e = 0; e < 16; e++) st[kt][e] = 0.f;
     {
-      bf16x8 k0 = HT::rows_frag(kimg, 0, 0, lane), k1 = HT::rows_frag(kimg, 32, 0, lane);
+      bf16x8 k0 = HT::rows_frag(kimg, fo, 0, 0), k1 = HT::rows_frag(kimg, fo, 32, 0);
 #pragma unroll
       for (int s = 0; s < KS; s++) {
         bf16x8 n0 = k0, n1 = k1;
-        if (s + 1 < KS) { n0 = HT::rows_frag(kimg, 0, s + 1, lane); n1 = HT::rows_frag(kimg, 32, s + 1, lane); }
+        if (s + 1 < KS) { n0 = HT::rows_frag(kimg, fo, 0, s + 1); n1 = HT::rows_frag(kimg, fo, 32, s + 1); }
         st[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[s], st[0], 0, 0, 0);
         st[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[s], st[1], 0, 0, 0);
         k0 = n0; k1 = n1;
@@ -198,13 +217,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // O^T += V^T P^T: 4 (kt, u) steps x DT independent accumulators, fragments one step ahead
     bf16x8 vf[DT];
 #pragma unroll
-    for (int t = 0; t < DT; t++) vf[t] = HT::cols_frag(vimg, 0, 0, t, lane);
+    for (int t = 0; t < DT; t++) vf[t] = HT::cols_frag(vimg, fo, 0, 0, t);
 #pragma unroll
     for (int ku = 0; ku < 4; ku++) {
       const bf16x8 pb = pack8(st[ku >> 1], ku & 1);
       bf16x8 nf[DT];
 #pragma unroll
-      for (int t = 0; t < DT; t++) nf[t] = ku < 3 ? HT::cols_frag(vimg, 32 * ((ku + 1) >> 1), (ku + 1) & 1, t, lane) : vf[t];
+      for (int t = 0; t < DT; t++) nf[t] = ku < 3 ? HT::cols_frag(vimg, fo, 32 * ((ku + 1) >> 1), (ku + 1) & 1, t) : vf[t];
 #pragma unroll
       for (int t = 0; t < DT; t++) ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t], pb, ot[t], 0, 0, 0);
 #pragma unroll
@@ -278,7 +297,9 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_kernel(AttnBwdParams p) {
       vfb[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, 32 * s + 2 * d, 0));
     }
   }
+  wait_vmem<0>();       // see the forward kernel: no compiler-inserted wait for these may remain inside the loop
 
+  const typename HT::Offsets fo = HT::offsets(lane);
   int c_row[NCH];
   unsigned cq_off[NCH], cd_off[NCH];
 #pragma unroll
@@ -300,11 +321,14 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_kernel(AttnBwdParams p) {
       dma16(slot + wave * 1024 + c * 4096, dq, ok ? cq_off[c] : kOob);
       dma16(slot + IMG + wave * 1024 + c * 4096, dd, ok ? cd_off[c] : kOob);
     }
-    if (tid < 2 * BQ) {                                       // row statistics of the step: lse[0..63], delta[0..63]
-      const int r = tid & (BQ - 1), q = q0 + r;
-      float v = 0.f;
-      if (q < p.S) v = tid < BQ ? p.lse[bh * p.S + q] : p.delta[(tok0 + q) * p.H + h];
-      reinterpret_cast<lds_f32*>(lds + ((i - step0) & 1) * SLOT + 2 * IMG)[tid] = v;
+    // row statistics of the step, by the same asynchronous path (a register load here would make the compiler wait
+    // for every copy just issued): wave 0 fetches lse[0..63], wave 1 delta[0..63], one dword per lane
+    if (wave < 2) {
+      const int q = q0 + lane;
+      const u32x4 ds = wave == 0 ? make_desc(p.lse + bh * p.S, (uint32_t)(p.S * 4))
+                                 : make_desc(p.delta + tok0 * p.H + h, (uint32_t)(((long)(p.S - 1) * p.H + 1) * 4));
+      const unsigned off = q < p.S ? (unsigned)(wave == 0 ? q * 4 : (long)q * p.H * 4) : kOob;
+      dma4(slot + 2 * IMG + wave * 256, ds, off);
     }
   };
 
@@ -314,68 +338,72 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_kernel(AttnBwdParams p) {
 #pragma unroll
     for (int e = 0; e < 16; e++) { dvt[t][e] = 0.f; dkt[t][e] = 0.f; }
 
-  bf16_t* const dst_row = p.dst + (bh * p.S + key) * p.S;     // dS^T row of the lane's key
+  // dS^T of this (sequence, head) through a buffer resource: the lane's key row and half are the vector offset, the
+  // query of a register group the scalar one; keys past the end are redirected out of range (dropped)
+  const __amdgpu_buffer_rsrc_t rst = make_rsrc(p.dst + bh * p.S * p.S, (uint32_t)((long)p.S * p.S * 2));
+  const unsigned st_off = key < p.S ? (unsigned)(((long)key * p.S + 4 * g) * 2) : kOob;
+  // One loop over 32-query tiles (two per step); the barrier and the next step's copies come with every even tile.
+  const int ntile = (p.S + 31) / 32;
   if (step0 < nstep) issue(step0);
-  for (int i = step0; i < nstep; i++) {
-    wait_vmem<0>();
-    __syncthreads();
-    if (i + 1 < nstep) issue(i + 1);
-    lds_u8* const qimg = lds + ((i - step0) & 1) * SLOT;
+  for (int tile = 2 * step0; tile < ntile; tile++) {
+    const int i = tile >> 1, qt = tile & 1;
+    if (qt == 0) {
+      wait_vmem<0>();
+      __syncthreads();
+      if (i + 1 < nstep) issue(i + 1);
+    }
+    lds_u8* const qimg = lds + ((i - step0) & 1) * SLOT + qt * 32 * HT::RB;     // this tile's 32 rows of the Q image
     lds_u8* const dimg = qimg + IMG;
-    const lds_f32* const stat = reinterpret_cast<const lds_f32*>(qimg + 2 * IMG);
-#pragma unroll
-    for (int qt = 0; qt < 2; qt++) {
-      const int qt0 = i * BQ + 32 * qt;                         // first query of the tile
-      if (qt0 >= p.S) continue;
-      if (p.causal && qt0 + 31 < kw0) {                         // every query of the tile is before every key of this wave:
-        if (key < p.S) {                                        // the tile of dS^T is zero
-#pragma unroll
-          for (int e4 = 0; e4 < 4; e4++) {
-            const int q = qt0 + 8 * e4 + 4 * g;
-            if (q < p.S) *reinterpret_cast<u32x2*>(dst_row + q) = u32x2{0u, 0u};
-          }
-        }
-        continue;
-      }
+    const lds_f32* const stat = reinterpret_cast<const lds_f32*>(lds + ((i - step0) & 1) * SLOT + 2 * IMG) + 32 * qt;
+    const int qt0 = tile * 32;                                  // first query of the tile
+    {   // (tiles whose queries are all before this wave's keys are not skipped: they come out as exact zeros, at most
+        // three tiles per workgroup, and the loop body stays one straight line)
       f32x16 sa, da;
 #pragma unroll
       for (int e = 0; e < 16; e++) { sa[e] = 0.f; da[e] = 0.f; }
       {
-        bf16x8 fq = HT::rows_frag(qimg, 32 * qt, 0, lane), fd = HT::rows_frag(dimg, 32 * qt, 0, lane);
+        bf16x8 fq = HT::rows_frag(qimg, fo, 0, 0), fd = HT::rows_frag(dimg, fo, 0, 0);
 #pragma unroll
         for (int s = 0; s < KS; s++) {
           bf16x8 nq = fq, nd = fd;
-          if (s + 1 < KS) { nq = HT::rows_frag(qimg, 32 * qt, s + 1, lane); nd = HT::rows_frag(dimg, 32 * qt, s + 1, lane); }
+          if (s + 1 < KS) { nq = HT::rows_frag(qimg, fo, 0, s + 1); nd = HT::rows_frag(dimg, fo, 0, s + 1); }
           sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq, kfb[s], sa, 0, 0, 0);
           da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd, vfb[s], da, 0, 0, 0);
           fq = nq; fd = nd;
         }
       }
-      // P and dS in place: register e is query qt0 + 8 (e / 4) + 4 g + e % 4, statistics fetched four rows at a time
-      const bool diag = p.causal && qt0 < kw0 + 31;             // some (query, key) pairs of the tile are masked
+      // P and dS in place: register e is query qt0 + 8 (e / 4) + 4 g + e % 4, statistics fetched four rows at a time;
+      // rel: the last register row (relative to 4 g) whose query is still before the lane's key
+      const int rel = p.causal ? key - qt0 - 4 * g : -1;
 #pragma unroll
       for (int e4 = 0; e4 < 4; e4++) {
-        const f32x4 ls = *reinterpret_cast<const LDS_AS f32x4*>(stat + 32 * qt + 8 * e4 + 4 * g);
-        const f32x4 dl = *reinterpret_cast<const LDS_AS f32x4*>(stat + BQ + 32 * qt + 8 * e4 + 4 * g);
+        const f32x4 ls = *reinterpret_cast<const LDS_AS f32x4*>(stat + 8 * e4 + 4 * g);
+        const f32x4 dl = *reinterpret_cast<const LDS_AS f32x4*>(stat + BQ + 8 * e4 + 4 * g);
 #pragma unroll
         for (int r = 0; r < 4; r++) {
           const int e = 4 * e4 + r;
           float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sa[e], p.scale_log2e, -ls[r]));
-          if (diag && key > qt0 + 8 * e4 + 4 * g + r) pe = 0.f;
+          pe = (8 * e4 + r < rel) ? 0.f : pe;                   // query before the key: masked
           sa[e] = pe;
           da[e] = pe * (da[e] - dl[r]);
         }
       }
       // dS^T out: four consecutive queries of the lane's key row per register group
-      if (key < p.S) {
+      u32x2 dsv[4];
 #pragma unroll
-        for (int e4 = 0; e4 < 4; e4++) {
-          const int q = qt0 + 8 * e4 + 4 * g;
-          bf16x4 v;
+      for (int e4 = 0; e4 < 4; e4++) {
+        bf16x4 v;
 #pragma unroll
-          for (int r = 0; r < 4; r++) v[r] = (bf16_t)da[4 * e4 + r];
-          if (q < p.S) *reinterpret_cast<bf16x4*>(dst_row + q) = v;
-        }
+        for (int r = 0; r < 4; r++) v[r] = (bf16_t)da[4 * e4 + r];
+        dsv[e4] = __builtin_bit_cast(u32x2, v);
+      }
+      if (qt0 + 32 <= p.S) {
+#pragma unroll
+        for (int e4 = 0; e4 < 4; e4++) __builtin_amdgcn_raw_buffer_store_b64(dsv[e4], rst, st_off, (qt0 + 8 * e4) * 2, 0);
+      } else {                                                  // ragged last tile (seq is a multiple of 8)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; e4++)
+          if (qt0 + 8 * e4 < p.S) __builtin_amdgcn_raw_buffer_store_b64(dsv[e4], rst, st_off, (qt0 + 8 * e4) * 2, 0);
       }
       // dV^T += dO^T P, dK^T += Q^T dS
 #pragma unroll
@@ -383,8 +411,8 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_kernel(AttnBwdParams p) {
         const bf16x8 pb = pack8(sa, u), sb = pack8(da, u);
 #pragma unroll
         for (int t = 0; t < DT; t++) {
-          dvt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HT::cols_frag(dimg, 32 * qt, u, t, lane), pb, dvt[t], 0, 0, 0);
-          dkt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HT::cols_frag(qimg, 32 * qt, u, t, lane), sb, dkt[t], 0, 0, 0);
+          dvt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HT::cols_frag(dimg, fo, 0, u, t), pb, dvt[t], 0, 0, 0);
+          dkt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HT::cols_frag(qimg, fo, 0, u, t), sb, dkt[t], 0, 0, 0);
         }
       }
     }

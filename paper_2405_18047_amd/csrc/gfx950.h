@@ -48,6 +48,12 @@ __device__ __forceinline__ void dma16(uint32_t lds_base, u32x4 desc, uint32_t vo
                :: "s"(lds_base), "v"(voff), "s"(desc) : "memory");
 }
 
+// The same with 4 bytes per lane: lane i's dword lands at lds_base + 4*i.
+__device__ __forceinline__ void dma4(uint32_t lds_base, u32x4 desc, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+               :: "s"(lds_base), "v"(voff), "s"(desc) : "memory");
+}
+
 template <int N> __device__ __forceinline__ void wait_vmem() {   // at most N vector-memory operations outstanding
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
 }

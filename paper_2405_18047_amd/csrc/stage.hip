@@ -36,12 +36,13 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Tensors needed only from forward to backward-p1 ("A" class) live in per-slot buffers handed out by a small
 // free list; a slot is taken at forward and returned at the end of backward-p1.
 enum WTensor { W_H1, W_A, W_H2, W_M, W_DQKV, W_DX1, W_DGU, W_DX2, W_COUNT };
-enum ATensor { A_X0, A_QKV, A_P, A_X1, A_GU, A_COUNT };
+enum ATensor { A_X0, A_QKV, A_P, A_LSE, A_X1, A_GU, A_COUNT };
 
 struct Dims {
   int L, d, H, dh, f, S, B, T, Mmax, slots, dtype, causal;
   size_t e;       // bytes per stored element
   bool attn;
+  bool fused;     // attention without stored probabilities (row log-sum-exp only)
   float eps, base;
 };
 
@@ -57,13 +58,14 @@ size_t w_width(const Dims& c, int t) {
 }
 bool w_from_forward(int t) { return t == W_H1 || t == W_A || t == W_H2 || t == W_M; }
 
-size_t a_elems(const Dims& c, int t) {      // elements per slot
+size_t a_bytes(const Dims& c, int t) {      // bytes per slot
   switch (t) {
-    case A_X0: return c.attn ? (size_t)c.T * c.d : 0;
-    case A_QKV: return c.attn ? (size_t)c.T * 3 * c.d : 0;
-    case A_P: return c.attn ? (size_t)c.B * c.H * c.S * c.S : 0;
-    case A_X1: return (size_t)c.T * c.d;
-    case A_GU: return (size_t)c.T * 2 * c.f;
+    case A_X0: return c.attn ? (size_t)c.T * c.d * c.e : 0;
+    case A_QKV: return c.attn ? (size_t)c.T * 3 * c.d * c.e : 0;
+    case A_P: return (c.attn && !c.fused) ? (size_t)c.B * c.H * c.S * c.S * c.e : 0;
+    case A_LSE: return (c.attn && c.fused) ? (size_t)c.B * c.H * c.S * sizeof(float) : 0;
+    case A_X1: return (size_t)c.T * c.d * c.e;
+    case A_GU: return (size_t)c.T * 2 * c.f * c.e;
   }
   return 0;
 }
@@ -96,7 +98,7 @@ Layout plan(const Dims& c) {
   off = 0;
   for (int t = 0; t < A_COUNT; t++) {
     y.a_off[t] = off;
-    off += align_up(a_elems(c, t) * c.e, 256);
+    off += align_up(a_bytes(c, t), 256);
   }
   y.a_slot_bytes = off;
   y.a_base = y.w_total;
@@ -106,7 +108,8 @@ Layout plan(const Dims& c) {
   y.ws_t_f = off; off += align_up((size_t)c.T * c.f * c.e, 256);
   y.ws_t_d0 = off; off += align_up((size_t)c.T * c.d * c.e, 256);
   y.ws_t_d1 = off; off += align_up((size_t)c.T * c.d * c.e, 256);
-  y.ws_scores = off; off += c.attn ? align_up((size_t)c.B * c.H * c.S * c.S * sizeof(float), 256) : 0;
+  // fp32 scores, then dS (materialised attention) or dS^T in the storage type (fused)
+  y.ws_scores = off; off += c.attn ? align_up((size_t)c.B * c.H * c.S * c.S * (c.fused ? c.e : sizeof(float)), 256) : 0;
   y.ws_norm_partials = off; off += align_up((size_t)tbp::kNormPartialBlocks * c.d * sizeof(float), 256);
   y.ws_rope = off; off += c.attn ? align_up((size_t)c.S * (c.dh / 2) * sizeof(float2), 256) : 0;
   y.ws_delta = off; off += c.attn ? align_up((size_t)c.T * c.H * sizeof(float), 256) : 0;
@@ -120,7 +123,7 @@ Layout plan(const Dims& c) {
   y.w_fwd_bytes_per_mb = fw * c.L;
   y.w_p1_bytes_per_mb = (p1 + (c.attn ? 2 : 1) * (size_t)c.d * sizeof(float)) * c.L;
   size_t a = 0;
-  for (int t = 0; t < A_COUNT; t++) a += a_elems(c, t) * c.e;
+  for (int t = 0; t < A_COUNT; t++) a += a_bytes(c, t);
   y.a_bytes_per_mb = a * c.L;
   return y;
 }
@@ -148,6 +151,13 @@ tbp_status check_config(const tbp_config* cfg, Dims* out) {
     if (c.S % q) return fail(TBP_EINVAL, "seq must be a multiple of %d for this dtype", q);
     if (c.S > tbp::kMaxSeq) return fail(TBP_EINVAL, "seq %d above the limit %d", c.S, tbp::kMaxSeq);
     if (!(c.base > 0.f)) return fail(TBP_EINVAL, "rope_base must be positive");
+  }
+  if (cfg->attention < TBP_ATTN_AUTO || cfg->attention > TBP_ATTN_FUSED) return fail(TBP_EINVAL, "attention must be a tbp_attention value");
+  {
+    const bool can_fuse = c.attn && c.dtype == TBP_BF16 && (c.dh == 64 || c.dh == 128);
+    if (cfg->attention == TBP_ATTN_FUSED && c.attn && !can_fuse)
+      return fail(TBP_EINVAL, "fused attention needs bf16 storage and head_dim 64 or 128");
+    c.fused = can_fuse && cfg->attention != TBP_ATTN_MATERIALISED;
   }
   if (!(c.eps >= 0.f)) return fail(TBP_EINVAL, "rms_eps must be >= 0");
   if ((long)c.S * c.B > (1L << 24)) return fail(TBP_EINVAL, "tokens per micro-batch above 2^24");
@@ -218,27 +228,31 @@ tbp_status run_forward(tbp_stage* st, int mb, int slot, const void* x_in, void* 
       void* qkv = st->aslot(l, A_QKV, slot);
       void* P = st->aslot(l, A_P, slot);
       void* a = st->wslab(l, W_A, mb);
-      float* scores = (float*)st->ws(st->y.ws_scores);
       TBP_HIP(tbp::rmsnorm_fwd(dt, T, d, c.eps, x0, st->g1[l], h1, s));
       TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NN, T, 3 * d, d, h1, d, st->w_qkv[l], 3 * d, qkv, 3 * d), s));
       TBP_HIP(tbp::rope(dt, T, c.S, 2 * c.H, c.dh, 3 * d, (const float2*)st->ws(st->y.ws_rope), 0, qkv, s));
-      {  // scores = q k^T / sqrt(dh), fp32
-        GemmArgs g = head_gemm(c, tbp::NT, c.S, c.S, c.dh);
-        g.alpha = 1.f / sqrtf((float)c.dh);
-        g.A = qkv; g.lda = 3 * d; g.sAo = (long)c.S * 3 * d; g.sAi = c.dh;
-        g.B = (const char*)qkv + (size_t)d * c.e; g.ldb = 3 * d; g.sBo = g.sAo; g.sBi = c.dh;
-        g.C = scores; g.ldc = c.S; g.sCo = (long)c.H * c.S * c.S; g.sCi = (long)c.S * c.S;
-        g.out_f32 = 1; g.causal = c.causal ? tbp::CAUSAL_SKIP_UPPER : tbp::CAUSAL_NONE;
-        TBP_HIP(tbp::gemm(dt, g, s));
-      }
-      TBP_HIP(tbp::softmax_fwd(dt, (long)c.B * c.H * c.S, c.S, c.causal, scores, P, s));
-      {  // a = P v
-        GemmArgs g = head_gemm(c, tbp::NN, c.S, c.dh, c.S);
-        g.A = P; g.lda = c.S; g.sAo = (long)c.H * c.S * c.S; g.sAi = (long)c.S * c.S;
-        g.B = (const char*)qkv + (size_t)2 * d * c.e; g.ldb = 3 * d; g.sBo = (long)c.S * 3 * d; g.sBi = c.dh;
-        g.C = a; g.ldc = d; g.sCo = (long)c.S * d; g.sCi = c.dh;
-        g.causal = c.causal ? tbp::CAUSAL_K_END : tbp::CAUSAL_NONE;
-        TBP_HIP(tbp::gemm(dt, g, s));
+      if (c.fused) {
+        TBP_HIP(tbp::attention_fwd(c.B, c.H, c.S, c.dh, c.causal, qkv, 3 * d, a, d, (float*)st->aslot(l, A_LSE, slot), s));
+      } else {
+        float* scores = (float*)st->ws(st->y.ws_scores);
+        {  // scores = q k^T / sqrt(dh), fp32
+          GemmArgs g = head_gemm(c, tbp::NT, c.S, c.S, c.dh);
+          g.alpha = 1.f / sqrtf((float)c.dh);
+          g.A = qkv; g.lda = 3 * d; g.sAo = (long)c.S * 3 * d; g.sAi = c.dh;
+          g.B = (const char*)qkv + (size_t)d * c.e; g.ldb = 3 * d; g.sBo = g.sAo; g.sBi = c.dh;
+          g.C = scores; g.ldc = c.S; g.sCo = (long)c.H * c.S * c.S; g.sCi = (long)c.S * c.S;
+          g.out_f32 = 1; g.causal = c.causal ? tbp::CAUSAL_SKIP_UPPER : tbp::CAUSAL_NONE;
+          TBP_HIP(tbp::gemm(dt, g, s));
+        }
+        TBP_HIP(tbp::softmax_fwd(dt, (long)c.B * c.H * c.S, c.S, c.causal, scores, P, s));
+        {  // a = P v
+          GemmArgs g = head_gemm(c, tbp::NN, c.S, c.dh, c.S);
+          g.A = P; g.lda = c.S; g.sAo = (long)c.H * c.S * c.S; g.sAi = (long)c.S * c.S;
+          g.B = (const char*)qkv + (size_t)2 * d * c.e; g.ldb = 3 * d; g.sBo = (long)c.S * 3 * d; g.sBi = c.dh;
+          g.C = a; g.ldc = d; g.sCo = (long)c.S * d; g.sCi = c.dh;
+          g.causal = c.causal ? tbp::CAUSAL_K_END : tbp::CAUSAL_NONE;
+          TBP_HIP(tbp::gemm(dt, g, s));
+        }
       }
       {  // x1 = x0 + a Wo
         GemmArgs g = gemm_args(tbp::NN, T, d, d, a, d, st->w_o[l], d, x1, d);
@@ -298,44 +312,51 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
     const long hs = (long)c.S * c.S, bs = (long)c.H * hs, tok3 = (long)c.S * 3 * d;
     // da = dx1 Wo^T
     TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NT, T, d, d, dx1, d, st->w_o[l], d, da, d), s));
-    // rowsum(dP * P) per (token, head) = rowsum(da * a): no S x S tensor needed for it
-    float* delta = (float*)st->ws(st->y.ws_delta);
-    TBP_HIP(tbp::head_rowdot(dt, T, c.H, c.dh, da, st->wslab(l, W_A, mb), delta, s));
-    {  // dS = P * (da v^T - delta): the softmax backward is the epilogue of the dP product (dP is never stored)
-      GemmArgs g = head_gemm(c, tbp::NT, c.S, c.S, c.dh);
-      g.A = da; g.lda = d; g.sAo = (long)c.S * d; g.sAi = c.dh;
-      g.B = (const char*)qkv + (size_t)2 * d * c.e; g.ldb = 3 * d; g.sBo = tok3; g.sBi = c.dh;
-      g.C = dP; g.ldc = c.S; g.sCo = bs; g.sCi = hs;
-      g.R = P;
-      g.delta = delta; g.ldd = c.H; g.sDo = (long)c.S * c.H; g.sDi = 1; g.delta_causal = c.causal;
-      g.causal = c.causal ? tbp::CAUSAL_SKIP_UPPER : tbp::CAUSAL_NONE;
-      TBP_HIP(tbp::gemm(dt, g, s));
-    }
-    {  // dv = P^T da
-      GemmArgs g = head_gemm(c, tbp::TN, c.S, c.dh, c.S);
-      g.A = P; g.lda = c.S; g.sAo = bs; g.sAi = hs;
-      g.B = da; g.ldb = d; g.sBo = (long)c.S * d; g.sBi = c.dh;
-      g.C = (char*)dqkv + (size_t)2 * d * c.e; g.ldc = 3 * d; g.sCo = tok3; g.sCi = c.dh;
-      g.causal = c.causal ? tbp::CAUSAL_K_BEGIN : tbp::CAUSAL_NONE;
-      TBP_HIP(tbp::gemm(dt, g, s));
-    }
-    {  // dq = dS k / sqrt(dh)
-      GemmArgs g = head_gemm(c, tbp::NN, c.S, c.dh, c.S);
-      g.alpha = scale;
-      g.A = dP; g.lda = c.S; g.sAo = bs; g.sAi = hs;
-      g.B = (const char*)qkv + (size_t)d * c.e; g.ldb = 3 * d; g.sBo = tok3; g.sBi = c.dh;
-      g.C = dqkv; g.ldc = 3 * d; g.sCo = tok3; g.sCi = c.dh;
-      g.causal = c.causal ? tbp::CAUSAL_K_END : tbp::CAUSAL_NONE;
-      TBP_HIP(tbp::gemm(dt, g, s));
-    }
-    {  // dk = dS^T q / sqrt(dh)
-      GemmArgs g = head_gemm(c, tbp::TN, c.S, c.dh, c.S);
-      g.alpha = scale;
-      g.A = dP; g.lda = c.S; g.sAo = bs; g.sAi = hs;
-      g.B = qkv; g.ldb = 3 * d; g.sBo = tok3; g.sBi = c.dh;
-      g.C = (char*)dqkv + (size_t)d * c.e; g.ldc = 3 * d; g.sCo = tok3; g.sCi = c.dh;
-      g.causal = c.causal ? tbp::CAUSAL_K_BEGIN : tbp::CAUSAL_NONE;
-      TBP_HIP(tbp::gemm(dt, g, s));
+    if (c.fused) {
+      // probabilities rebuilt from the stashed row log-sum-exp; dq, dk, dv straight into the dqkv slab
+      TBP_HIP(tbp::attention_p1(c.B, c.H, c.S, c.dh, c.causal, qkv, 3 * d, st->wslab(l, W_A, mb), da, d,
+                                (const float*)st->aslot(l, A_LSE, slot), dqkv, 3 * d, (float*)st->ws(st->y.ws_delta),
+                                dP, s));
+    } else {
+      // rowsum(dP * P) per (token, head) = rowsum(da * a): no S x S tensor needed for it
+      float* delta = (float*)st->ws(st->y.ws_delta);
+      TBP_HIP(tbp::head_rowdot(dt, T, c.H, c.dh, da, st->wslab(l, W_A, mb), delta, s));
+      {  // dS = P * (da v^T - delta): the softmax backward is the epilogue of the dP product (dP is never stored)
+        GemmArgs g = head_gemm(c, tbp::NT, c.S, c.S, c.dh);
+        g.A = da; g.lda = d; g.sAo = (long)c.S * d; g.sAi = c.dh;
+        g.B = (const char*)qkv + (size_t)2 * d * c.e; g.ldb = 3 * d; g.sBo = tok3; g.sBi = c.dh;
+        g.C = dP; g.ldc = c.S; g.sCo = bs; g.sCi = hs;
+        g.R = P;
+        g.delta = delta; g.ldd = c.H; g.sDo = (long)c.S * c.H; g.sDi = 1; g.delta_causal = c.causal;
+        g.causal = c.causal ? tbp::CAUSAL_SKIP_UPPER : tbp::CAUSAL_NONE;
+        TBP_HIP(tbp::gemm(dt, g, s));
+      }
+      {  // dv = P^T da
+        GemmArgs g = head_gemm(c, tbp::TN, c.S, c.dh, c.S);
+        g.A = P; g.lda = c.S; g.sAo = bs; g.sAi = hs;
+        g.B = da; g.ldb = d; g.sBo = (long)c.S * d; g.sBi = c.dh;
+        g.C = (char*)dqkv + (size_t)2 * d * c.e; g.ldc = 3 * d; g.sCo = tok3; g.sCi = c.dh;
+        g.causal = c.causal ? tbp::CAUSAL_K_BEGIN : tbp::CAUSAL_NONE;
+        TBP_HIP(tbp::gemm(dt, g, s));
+      }
+      {  // dq = dS k / sqrt(dh)
+        GemmArgs g = head_gemm(c, tbp::NN, c.S, c.dh, c.S);
+        g.alpha = scale;
+        g.A = dP; g.lda = c.S; g.sAo = bs; g.sAi = hs;
+        g.B = (const char*)qkv + (size_t)d * c.e; g.ldb = 3 * d; g.sBo = tok3; g.sBi = c.dh;
+        g.C = dqkv; g.ldc = 3 * d; g.sCo = tok3; g.sCi = c.dh;
+        g.causal = c.causal ? tbp::CAUSAL_K_END : tbp::CAUSAL_NONE;
+        TBP_HIP(tbp::gemm(dt, g, s));
+      }
+      {  // dk = dS^T q / sqrt(dh)
+        GemmArgs g = head_gemm(c, tbp::TN, c.S, c.dh, c.S);
+        g.alpha = scale;
+        g.A = dP; g.lda = c.S; g.sAo = bs; g.sAi = hs;
+        g.B = qkv; g.ldb = 3 * d; g.sBo = tok3; g.sBi = c.dh;
+        g.C = (char*)dqkv + (size_t)d * c.e; g.ldc = 3 * d; g.sCo = tok3; g.sCi = c.dh;
+        g.causal = c.causal ? tbp::CAUSAL_K_BEGIN : tbp::CAUSAL_NONE;
+        TBP_HIP(tbp::gemm(dt, g, s));
+      }
     }
     TBP_HIP(tbp::rope(dt, T, c.S, 2 * c.H, c.dh, 3 * d, (const float2*)st->ws(st->y.ws_rope), 1, dqkv, s));
     // dh1 = [dq, dk, dv] Wqkv^T

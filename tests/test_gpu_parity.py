@@ -220,8 +220,8 @@ def _stage_inputs(shape):
     return params, xs, dys
 
 
-def _run_gpu(shape, params, xs, dys, mode=tbp.TBP_P2_LOOP, accumulate=True, p1_order=None):
-    st = make_gpu_stage(shape, params)
+def _run_gpu(shape, params, xs, dys, mode=tbp.TBP_P2_LOOP, accumulate=True, p1_order=None, attention=tbp.TBP_ATTN_AUTO):
+    st = make_gpu_stage(shape, params, attention=attention)
     n = len(xs)
     outs = [st.forward(m, to_dev(xs[m], shape.dtype)) for m in range(n)]
     dxs = [None] * n
@@ -242,15 +242,21 @@ SMALL = {
 }
 
 
-@pytest.mark.parametrize("name", list(SMALL))
+# the attention of the bf16 stages with head_dim 64 / 128 runs fused by default; the same stages are also run with the
+# materialised form (probabilities stashed)
+STAGE_CASES = [(n, tbp.TBP_ATTN_AUTO) for n in SMALL] + [("small_bf16", tbp.TBP_ATTN_MATERIALISED),
+                                                        ("tiles_bf16", tbp.TBP_ATTN_MATERIALISED)]
+
+
+@pytest.mark.parametrize("name,attention", STAGE_CASES)
 @pytest.mark.parametrize("mode", [tbp.TBP_P2_LOOP, tbp.TBP_P2_KCONCAT])
-def test_stage_matches_oracle(name, mode):
+def test_stage_matches_oracle(name, attention, mode):
     shape = SMALL[name]
-    _say(f"stage {name} mode={mode} shape={shape}")
+    _say(f"stage {name} mode={mode} attention={attention} shape={shape}")
     params, xs, dys = _stage_inputs(shape)
     outs, dxs, grads = run_oracle(shape, params, xs, dys)
     st, g_outs, g_dxs = _run_gpu(shape, params, xs, dys, mode=mode, accumulate=False,
-                                 p1_order=list(reversed(range(len(xs)))))
+                                 p1_order=list(reversed(range(len(xs)))), attention=attention)
     compare_stage(shape, g_outs, g_dxs, st.grads, outs, dxs, grads, stage_tolerance(shape.dtype), f"{name}/{mode}")
     stats = st.stats()
     assert stats["w_live_bytes"] == 0 and stats["a_live_bytes"] == 0 and stats["high_water_bytes"] > 0

@@ -37,11 +37,16 @@ def test_stash_sizes_follow_the_stash_rule():
         else:
             w_el = 2 * d + 3 * f
             a_el = d + 2 * f
-        got = _sizes(s)
+        got = _sizes(s, attention=tbp.TBP_ATTN_MATERIALISED)
         w_expect = L * M * T * w_el * 2
         assert w_expect <= got["w_stash_bytes"] <= w_expect * 1.001 + L * 2 * M * d * 4 + 4096 * L
         assert got["a_stash_bytes"] == L * M * T * a_el * 2
         assert got["arena_bytes"] >= got["w_stash_bytes"] + got["a_stash_bytes"] + got["workspace_bytes"]
+        if s.n_heads:     # fused attention keeps a row log-sum-exp (fp32 per token and head) instead of the probabilities
+            fused = _sizes(s, attention=tbp.TBP_ATTN_FUSED)
+            assert fused["a_stash_bytes"] == L * M * T * ((5 * d + 2 * f) * 2 + s.n_heads * 4)
+            assert fused["w_stash_bytes"] == got["w_stash_bytes"]
+            assert _sizes(s)["a_stash_bytes"] == fused["a_stash_bytes"]       # AUTO picks it for bf16, head_dim 128
     # fewer activation slots shrink only the forward->p1 part
     s = si.CONFIGS["llama7b_s1024"]
     assert _sizes(s, act_slots=1)["a_stash_bytes"] * 4 == _sizes(s)["a_stash_bytes"]
@@ -51,13 +56,25 @@ def test_stash_sizes_follow_the_stash_rule():
 
 
 @pytest.mark.parametrize("field,value", [("d_model", 4100), ("d_ffn", 11004), ("seq", 4104), ("head_dim", 120),
-                                         ("n_layers", 0), ("dtype", 7), ("d_model", 16384), ("seq", 8192)])
+                                         ("n_layers", 0), ("dtype", 7), ("d_model", 16384), ("seq", 8192), ("attention", 3)])
 def test_bad_configs_are_rejected(field, value):
     cfg = tbp.config_from_shape(si.CONFIGS["llama7b_s1024"])
     setattr(cfg, field, value)
     with pytest.raises(tbp.TbpError) as e:
         tbp.tbp_stash_query(cfg)
     assert e.value.status == 1 and str(e.value)
+
+
+def test_fused_attention_is_refused_where_it_is_not_built():
+    cfg = tbp.config_from_shape(si.CONFIGS["tiny_f32"], attention=tbp.TBP_ATTN_FUSED)       # fp32 storage
+    with pytest.raises(tbp.TbpError) as e:
+        tbp.tbp_stash_query(cfg)
+    assert e.value.status == 1
+    cfg = tbp.config_from_shape(si.CONFIGS["llama7b_s1024"], attention=tbp.TBP_ATTN_FUSED)
+    cfg.n_heads, cfg.head_dim = 128, 32                                                       # head_dim 32
+    with pytest.raises(tbp.TbpError):
+        tbp.tbp_stash_query(cfg)
+    tbp.tbp_stash_query(tbp.config_from_shape(si.CONFIGS["tiny_f32"]))                       # AUTO falls back
 
 
 class _FakeStage:
