@@ -270,7 +270,7 @@ template <int DH>
 __global__ __launch_bounds__(256) void attn_bwd_kv_kernel(AttnBwdParams p) {
   using HT = HeadTile<DH>;
   constexpr int KS = DH / 16, DT = DH / 32, BQ = 64;
-  constexpr int IMG = BQ * HT::RB, SLOT = 2 * IMG + 1024;     // Q image, dO image, 64 x (lse, delta)
+  constexpr int IMG = BQ * HT::RB, SLOT = 2 * IMG + 1024;     // Q image, dO image, 64 x (lse, delta); three slots
   constexpr int NCH = IMG / 1024 / 4;
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
@@ -310,9 +310,9 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_kernel(AttnBwdParams p) {
   const int step0 = p.causal ? kv0 / BQ : 0;                  // queries before the first key of the block see none of it
   const int nstep = (p.S + BQ - 1) / BQ;
   typedef LDS_AS float lds_f32;
-  auto issue = [&](int i) {
+  auto issue = [&](int i, int slot_off) {          // step i into the slot at byte offset slot_off
     const int q0 = i * BQ;
-    const uint32_t slot = lds0 + ((i - step0) & 1) * SLOT;
+    const uint32_t slot = lds0 + slot_off;
     const u32x4 dq = make_desc(p.qkv + (tok0 + q0) * p.ld_qkv + h * DH, (uint32_t)((long)(p.S - q0) * p.ld_qkv * 2));
     const u32x4 dd = make_desc(p.dout + (tok0 + q0) * p.ld_do + h * DH, (uint32_t)((long)(p.S - q0) * p.ld_do * 2));
 #pragma unroll
@@ -342,79 +342,112 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_kernel(AttnBwdParams p) {
   // query of a register group the scalar one; keys past the end are redirected out of range (dropped)
   const __amdgpu_buffer_rsrc_t rst = make_rsrc(p.dst + bh * p.S * p.S, (uint32_t)((long)p.S * p.S * 2));
   const unsigned st_off = key < p.S ? (unsigned)(((long)key * p.S + 4 * g) * 2) : kOob;
-  // One loop over 32-query tiles (two per step); the barrier and the next step's copies come with every even tile.
-  const int ntile = (p.S + 31) / 32;
-  if (step0 < nstep) issue(step0);
-  for (int tile = 2 * step0; tile < ntile; tile++) {
-    const int i = tile >> 1, qt = tile & 1;
-    if (qt == 0) {
-      wait_vmem<0>();
-      __syncthreads();
-      if (i + 1 < nstep) issue(i + 1);
-    }
-    lds_u8* const qimg = lds + ((i - step0) & 1) * SLOT + qt * 32 * HT::RB;     // this tile's 32 rows of the Q image
+  // Three phases per 32-query tile: (1) S and dP on the matrix pipe, (2) P, dS, their bf16 forms and the dS^T store on
+  // the vector pipe, (3) dV^T and dK^T on the matrix pipe.  A wave runs them as a software pipeline three tiles deep -
+  // at time k: phase 1 of tile k, phase 2 of tile k-1, phase 3 of tile k-2, all independent of each other - so the vector
+  // work of one tile sits between the MFMAs of its neighbours instead of stalling the matrix pipe (one wave per SIMD:
+  // nothing else would fill it).  Two tiles per step of 64 queries, three slots: steps i (read by phases 2 and 3) and
+  // i+1 (read by phase 1) are live while step i+2 lands.
+  struct Raw { f32x16 s, d; };
+  struct Packed { bf16x8 p[2], s[2]; };
+  auto phase1 = [&](lds_u8* qimg, Raw& r) {                       // qimg: the tile's 32 rows of the step's Q image
     lds_u8* const dimg = qimg + IMG;
-    const lds_f32* const stat = reinterpret_cast<const lds_f32*>(lds + ((i - step0) & 1) * SLOT + 2 * IMG) + 32 * qt;
-    const int qt0 = tile * 32;                                  // first query of the tile
-    {   // (tiles whose queries are all before this wave's keys are not skipped: they come out as exact zeros, at most
-        // three tiles per workgroup, and the loop body stays one straight line)
-      f32x16 sa, da;
 #pragma unroll
-      for (int e = 0; e < 16; e++) { sa[e] = 0.f; da[e] = 0.f; }
-      {
-        bf16x8 fq = HT::rows_frag(qimg, fo, 0, 0), fd = HT::rows_frag(dimg, fo, 0, 0);
+    for (int e = 0; e < 16; e++) { r.s[e] = 0.f; r.d[e] = 0.f; }
+    // fragments requested PF k-steps ahead of their MFMA: an LDS read takes several MFMA issue slots to return
+    constexpr int PF = KS < 4 ? KS : 4;
+    bf16x8 fq[KS], fd[KS];
 #pragma unroll
-        for (int s = 0; s < KS; s++) {
-          bf16x8 nq = fq, nd = fd;
-          if (s + 1 < KS) { nq = HT::rows_frag(qimg, fo, 0, s + 1); nd = HT::rows_frag(dimg, fo, 0, s + 1); }
-          sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq, kfb[s], sa, 0, 0, 0);
-          da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd, vfb[s], da, 0, 0, 0);
-          fq = nq; fd = nd;
-        }
+    for (int s = 0; s < PF; s++) { fq[s] = HT::rows_frag(qimg, fo, 0, s); fd[s] = HT::rows_frag(dimg, fo, 0, s); }
+#pragma unroll
+    for (int s = 0; s < KS; s++) {
+      if (s + PF < KS) { fq[s + PF] = HT::rows_frag(qimg, fo, 0, s + PF); fd[s + PF] = HT::rows_frag(dimg, fo, 0, s + PF); }
+      r.s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[s], kfb[s], r.s, 0, 0, 0);
+      r.d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[s], vfb[s], r.d, 0, 0, 0);
+    }
+  };
+  // register e of a tile is query qt0 + 8 (e / 4) + 4 g + e % 4; statistics fetched four rows at a time
+  auto phase2 = [&](const lds_f32* stat, int qt0, const Raw& r, Packed& k) {   // arithmetic only; phase2_store writes dS^T
+    const int rel = p.causal ? key - qt0 - 4 * g : -1;            // register rows (relative to 4 g) below it: query before the key
+    float pv[16], sv[16];
+#pragma unroll
+    for (int e4 = 0; e4 < 4; e4++) {
+      const f32x4 ls = *reinterpret_cast<const LDS_AS f32x4*>(stat + 8 * e4 + 4 * g);
+      const f32x4 dl = *reinterpret_cast<const LDS_AS f32x4*>(stat + BQ + 8 * e4 + 4 * g);
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int e = 4 * e4 + q;
+        float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(r.s[e], p.scale_log2e, -ls[q]));
+        pe = (8 * e4 + q < rel) ? 0.f : pe;
+        pv[e] = pe;
+        sv[e] = pe * (r.d[e] - dl[q]);
       }
-      // P and dS in place: register e is query qt0 + 8 (e / 4) + 4 g + e % 4, statistics fetched four rows at a time;
-      // rel: the last register row (relative to 4 g) whose query is still before the lane's key
-      const int rel = p.causal ? key - qt0 - 4 * g : -1;
+    }
 #pragma unroll
-      for (int e4 = 0; e4 < 4; e4++) {
-        const f32x4 ls = *reinterpret_cast<const LDS_AS f32x4*>(stat + 8 * e4 + 4 * g);
-        const f32x4 dl = *reinterpret_cast<const LDS_AS f32x4*>(stat + BQ + 8 * e4 + 4 * g);
+    for (int u = 0; u < 2; u++)
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-          const int e = 4 * e4 + r;
-          float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sa[e], p.scale_log2e, -ls[r]));
-          pe = (8 * e4 + r < rel) ? 0.f : pe;                   // query before the key: masked
-          sa[e] = pe;
-          da[e] = pe * (da[e] - dl[r]);
-        }
+      for (int t = 0; t < 8; t++) { k.p[u][t] = (bf16_t)pv[8 * u + t]; k.s[u][t] = (bf16_t)sv[8 * u + t]; }
+  };
+  // dS^T out: the two halves of each packed k-step are four consecutive queries of the lane's key row
+  auto phase2_store = [&](int qt0, const Packed& k) {
+    const u32x4 s0 = __builtin_bit_cast(u32x4, k.s[0]), s1 = __builtin_bit_cast(u32x4, k.s[1]);
+    const u32x2 dsv[4] = {u32x2{s0[0], s0[1]}, u32x2{s0[2], s0[3]}, u32x2{s1[0], s1[1]}, u32x2{s1[2], s1[3]}};
+    if (qt0 + 32 <= p.S) {
+#pragma unroll
+      for (int e4 = 0; e4 < 4; e4++) __builtin_amdgcn_raw_buffer_store_b64(dsv[e4], rst, st_off, (qt0 + 8 * e4) * 2, 0);
+    } else {                                                      // ragged last tile (seq is a multiple of 8), or past the end
+#pragma unroll
+      for (int e4 = 0; e4 < 4; e4++)
+        if (qt0 + 8 * e4 < p.S) __builtin_amdgcn_raw_buffer_store_b64(dsv[e4], rst, st_off, (qt0 + 8 * e4) * 2, 0);
+    }
+  };
+  auto phase3 = [&](lds_u8* qimg, const Packed& k) {              // dV^T += dO^T P, dK^T += Q^T dS
+    lds_u8* const dimg = qimg + IMG;
+    constexpr int N = 2 * DT, PF = N < 3 ? N : 3;                 // (u, t) pairs; fragments requested PF pairs ahead
+    bf16x8 fo_d[N], fo_q[N];
+#pragma unroll
+    for (int j = 0; j < PF; j++) { fo_d[j] = HT::cols_frag(dimg, fo, 0, j / DT, j % DT); fo_q[j] = HT::cols_frag(qimg, fo, 0, j / DT, j % DT); }
+#pragma unroll
+    for (int j = 0; j < N; j++) {
+      if (j + PF < N) {
+        fo_d[j + PF] = HT::cols_frag(dimg, fo, 0, (j + PF) / DT, (j + PF) % DT);
+        fo_q[j + PF] = HT::cols_frag(qimg, fo, 0, (j + PF) / DT, (j + PF) % DT);
       }
-      // dS^T out: four consecutive queries of the lane's key row per register group
-      u32x2 dsv[4];
-#pragma unroll
-      for (int e4 = 0; e4 < 4; e4++) {
-        bf16x4 v;
-#pragma unroll
-        for (int r = 0; r < 4; r++) v[r] = (bf16_t)da[4 * e4 + r];
-        dsv[e4] = __builtin_bit_cast(u32x2, v);
+      dvt[j % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo_d[j], k.p[j / DT], dvt[j % DT], 0, 0, 0);
+      dkt[j % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo_q[j], k.s[j / DT], dkt[j % DT], 0, 0, 0);
+    }
+  };
+  auto stat_of = [&](int slot_off, int qt) { return reinterpret_cast<const lds_f32*>(lds + slot_off + 2 * IMG) + 32 * qt; };
+  constexpr int HALF = 32 * HT::RB;                               // the second tile's rows inside an image
+
+  if (step0 < nstep) {
+    int s_cur = 0, s_nxt = SLOT, s_far = 2 * SLOT;                // slots of step i, i+1, i+2
+    issue(step0, s_cur);
+    wait_vmem<0>();
+    __syncthreads();
+    if (step0 + 1 < nstep) issue(step0 + 1, s_nxt);
+    Raw r0, r1;
+    Packed k0, k1;
+    phase1(lds + s_cur, r0);                                      // time 2 step0
+    phase1(lds + s_cur + HALF, r1);                               // time 2 step0 + 1
+    phase2(stat_of(s_cur, 0), 2 * step0 * 32, r0, k0);
+    phase2_store(2 * step0 * 32, k0);
+    for (int i = step0; i < nstep; i++) {
+      // tiles 2i (packed in k0) and 2i+1 (raw in r1) are in flight; step i+1 must have landed for the next phase 1
+      if (i + 1 < nstep) {
+        wait_vmem<0>();
+        __syncthreads();                                          // also: every wave is done with step i-1 (slot s_far)
+        if (i + 2 < nstep) issue(i + 2, s_far);
       }
-      if (qt0 + 32 <= p.S) {
-#pragma unroll
-        for (int e4 = 0; e4 < 4; e4++) __builtin_amdgcn_raw_buffer_store_b64(dsv[e4], rst, st_off, (qt0 + 8 * e4) * 2, 0);
-      } else {                                                  // ragged last tile (seq is a multiple of 8)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; e4++)
-          if (qt0 + 8 * e4 < p.S) __builtin_amdgcn_raw_buffer_store_b64(dsv[e4], rst, st_off, (qt0 + 8 * e4) * 2, 0);
-      }
-      // dV^T += dO^T P, dK^T += Q^T dS
-#pragma unroll
-      for (int u = 0; u < 2; u++) {
-        const bf16x8 pb = pack8(sa, u), sb = pack8(da, u);
-#pragma unroll
-        for (int t = 0; t < DT; t++) {
-          dvt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HT::cols_frag(dimg, fo, 0, u, t), pb, dvt[t], 0, 0, 0);
-          dkt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HT::cols_frag(qimg, fo, 0, u, t), sb, dkt[t], 0, 0, 0);
-        }
-      }
+      phase1(lds + s_nxt, r0);                                    // tile 2i+2 (stale slot contents past the end: unused)
+      phase2(stat_of(s_cur, 1), (2 * i + 1) * 32, r1, k1);        // tile 2i+1
+      phase2_store((2 * i + 1) * 32, k1);
+      phase3(lds + s_cur, k0);                                    // tile 2i
+      phase1(lds + s_nxt + HALF, r1);                             // tile 2i+3
+      phase2(stat_of(s_nxt, 0), (2 * i + 2) * 32, r0, k0);        // tile 2i+2
+      phase2_store((2 * i + 2) * 32, k0);                         // (dropped past the end)
+      phase3(lds + s_cur + HALF, k1);                             // tile 2i+1
+      const int t = s_cur; s_cur = s_nxt; s_nxt = s_far; s_far = t;
     }
   }
 
@@ -462,7 +495,7 @@ hipError_t attention_fwd(int batch, int n_heads, int seq, int head_dim, int caus
 
 template <int DH>
 static hipError_t launch_bwd_kv(const AttnBwdParams& p, hipStream_t s) {
-  constexpr size_t smem = 2 * (2 * 64 * DH * 2 + 1024);
+  constexpr size_t smem = 3 * (2 * 64 * DH * 2 + 1024);
   auto kern = attn_bwd_kv_kernel<DH>;
   static bool attr_set = false;
   if (!attr_set) {
