@@ -239,7 +239,11 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   // Fragment fetch order = order of first use by the MFMA sequence (i-major): a0, then every b, then a1, a2, ...;
   // one fetch per MFMA from the start of the region, so the fragments the NEXT region needs first have the whole
   // region to arrive and the last fetches still have MM - UNITS MFMAs of cover.  The copies fill the second half.
-  auto region = [&](const bf16x8* fa, const bf16x8* fb, bf16x8* na, bf16x8* nb, lds_u8* st, int nks, const CopyJob* job) {
+  // job != null: copies c0 .. c1-1 of the job are issued, spread over MFMAs m0 .. MM-1 of the region
+  auto region = [&](const bf16x8* fa, const bf16x8* fb, bf16x8* na, bf16x8* nb, lds_u8* st, int nks, const CopyJob* job,
+                    int c0 = 0, int c1 = -1, int m0 = -1) {
+    if (c1 < 0) c1 = L;
+    if (m0 < 0) m0 = MM >= 2 * L ? MM - L : 0;
 #pragma unroll
     for (int m = 0; m < MM; m++) {
       const int i = m / TN, j = m % TN;
@@ -255,9 +259,9 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
         }
       }
       if (job) {
-        constexpr int C0 = MM >= 2 * L ? MM - L : 0;       // first MFMA that carries a copy
+        const int n = c1 - c0;
 #pragma unroll
-        for (int c = ((m - C0) * L) / (MM - C0); m >= C0 && c < ((m - C0 + 1) * L) / (MM - C0); c++) copy_one(*job, c);
+        for (int c = c0 + ((m - m0) * n) / (MM - m0); m >= m0 && c < c0 + ((m - m0 + 1) * n) / (MM - m0); c++) copy_one(*job, c);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -294,29 +298,34 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   } else {
     // 64-deep slots, two of them: four k-steps per iteration.  The barrier sits before the last k-step: by then every
     // wave has fetched its last fragments of slot t (they are multiplied from registers in the last k-step), so the
-    // barrier both publishes slot t+1 and frees slot t, whose refill with tile t+2 is issued during that last
-    // k-step and has a whole iteration to land.
+    // barrier both publishes slot t+1 and frees slot t for tile t+2.
+    // That refill is issued in two halves: one in the k-step after the barrier, one in the first k-step of the next
+    // iteration (it still has three k-steps to land), so the texture path sees no burst of 16 copies per wave.
+    // Invariant at the top of iteration t: tile t is landed or fully in flight, the first half of tile t+1 is in
+    // flight and j is the job of tile t+1.
     if (nk > 0) {
+      {
+        const CopyJob j0 = next_job();
 #pragma unroll
-      for (int t = 0; t < 2; t++) {
-        const CopyJob j = next_job();
-#pragma unroll
-        for (int c = 0; c < L; c++) copy_one(j, c);
+        for (int c = 0; c < L; c++) copy_one(j0, c);
       }
-      wait_vmem<L>();
+      CopyJob j = next_job();
+#pragma unroll
+      for (int c = 0; c < L / 2; c++) copy_one(j, c);
+      wait_vmem<L / 2>();                     // tile 0 has landed (this wave's share)
       __syncthreads();
       first_fragments();
       for (int t = 0; t < nk; t++) {
         lds_u8* const cur = lds + (t & 1) * STAGE_BYTES;
         lds_u8* const nxt = lds + ((t + 1) & 1) * STAGE_BYTES;
-        region(fa0, fb0, fa1, fb1, cur, 1, nullptr);
+        region(fa0, fb0, fa1, fb1, cur, 1, &j, L / 2, L, 0);
         region(fa1, fb1, fa0, fb0, cur, 2, nullptr);
         region(fa0, fb0, fa1, fb1, cur, 3, nullptr);
         wait_vmem<0>();                       // tile t+1 has landed (this wave's share)
         __syncthreads();
-        const CopyJob j = next_job();         // tile t + 2 into the slot of tile t
+        j = next_job();                       // tile t + 2 into the slot of tile t
         __builtin_amdgcn_sched_barrier(0);
-        region(fa1, fb1, fa0, fb0, nxt, 0, &j);
+        region(fa1, fb1, fa0, fb0, nxt, 0, &j, 0, L / 2, 0);
       }
       wait_vmem<0>();
     }
