@@ -48,6 +48,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="llama7b_s2048")
+    ap.add_argument("--gain-grad", choices=["partials", "literal"], default="partials",
+                    help="RMSNorm gain gradients: fp32 partials left by p1 and summed in p2 (default), or computed in p2 "
+                         "from stashed norm inputs and output derivatives")
     ap.add_argument("--attention", choices=["auto", "materialised", "fused"], default="auto",
                     help="attention of each layer: fused kernels keeping only a row log-sum-exp (the default where built) "
                          "or separate products with the probabilities stashed")
@@ -92,7 +95,8 @@ def main() -> int:
     xs = [randn(shape.tokens, d) for _ in range(M)]
     dys = [randn(shape.tokens, d) for _ in range(M)]
     attn = {"auto": tbp.TBP_ATTN_AUTO, "materialised": tbp.TBP_ATTN_MATERIALISED, "fused": tbp.TBP_ATTN_FUSED}[args.attention]
-    st = tbp.Stage(tbp.config_from_shape(shape, attention=attn), params, dev)
+    gain = tbp.TBP_GAIN_LITERAL if args.gain_grad == "literal" else tbp.TBP_GAIN_PARTIALS
+    st = tbp.Stage(tbp.config_from_shape(shape, attention=attn, gain_grad=gain), params, dev)
     x_out = torch.empty_like(xs[0])
     dx_out = torch.empty_like(xs[0])
 
@@ -166,7 +170,8 @@ def main() -> int:
                    "head_dim": shape.head_dim, "d_ffn": f, "seq": shape.seq, "micro_batch": shape.micro_batch,
                    "n_microbatches": M, "p2_mode": "k-concatenated, deferred until all p1 done",
                    "attention": ("none" if not shape.n_heads else "materialised" if args.attention == "materialised" else
-                                 "fused" if shape.dtype == "bf16" and shape.head_dim in (64, 128) else "materialised")},
+                                 "fused" if shape.dtype == "bf16" and shape.head_dim in (64, 128) else "materialised"),
+                   "gain_grad": args.gain_grad},
         "pct_of_bf16_mfma_peak": round(100.0 * p2_tflops / PEAK_BF16_TFLOPS, 2),
         "p2_ms": round(statistics.median(p2_ms), 3),
         "p2_loop_ms": None if args.no_loop_compare else round(statistics.median(p2_loop_ms), 3),

@@ -68,6 +68,15 @@ typedef enum { TBP_P2_LOOP = 0, TBP_P2_KCONCAT = 1 } tbp_p2_mode;
  *   AUTO          FUSED where it is available, MATERIALISED elsewhere. */
 typedef enum { TBP_ATTN_AUTO = 0, TBP_ATTN_MATERIALISED = 1, TBP_ATTN_FUSED = 2 } tbp_attention;
 
+/* Where the gradient of an RMSNorm gain, dg = sum over tokens of dy * x * rsqrt(mean(x^2) + eps), is computed.  A gain
+ * is a parameter, so by Section 3.1 its gradient is backward-p2 work; the two settings give the same result:
+ *   PARTIALS  p1, which has x and dy in registers anyway, leaves one fp32 [d_model] partial per norm and micro-batch
+ *             in the stash and p2 adds the partials of its set (no activation is kept for the norms past p1);
+ *   LITERAL   p1 computes nothing for the gains; each norm's input x and output derivative dy are stashed until p2
+ *             like a linear layer's operands (4 more [tokens, d_model] tensors per layer and micro-batch, 2 for an
+ *             MLP-only layer) and p2 computes dg from them, over the concatenated rows for KCONCAT. */
+typedef enum { TBP_GAIN_PARTIALS = 0, TBP_GAIN_LITERAL = 1 } tbp_gain_grad;
+
 typedef struct {
   int32_t n_layers;
   int32_t d_model;
@@ -84,6 +93,7 @@ typedef struct {
   float rms_eps;            /* added to the mean square inside the square root */
   float rope_base;
   int32_t attention;        /* tbp_attention: how the attention of each layer is computed and what it stashes */
+  int32_t gain_grad;        /* tbp_gain_grad: which phase computes the RMSNorm gain gradients */
 } tbp_config;
 
 /* Per-layer arrays (host arrays of length n_layers holding DEVICE pointers).  The w_* / g* arrays hold
@@ -169,6 +179,10 @@ tbp_status tbp_rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x,
 tbp_status tbp_rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
                           const void* resid, void* dx, float* dg_out, void* scratch, void* stream);
 size_t tbp_rmsnorm_p1_scratch_bytes(int d);
+/* The gain gradient alone, as a backward-p2 operation (Section 3.1): dg_out [d] fp32 (= or +=) sum over rows of
+ * dy * x * rsqrt(mean(x^2) + eps).  dy, x [rows, d] device, storage type; scratch as for tbp_rmsnorm_p1. */
+tbp_status tbp_rmsnorm_gain_p2(int dtype, int rows, int d, float eps, const void* dy, const void* x, int accumulate,
+                               float* dg_out, void* scratch, void* stream);
 /* gu [rows, 2f] (gate | up) -> m [rows, f];  p1: dm [rows, f], gu -> dgu [rows, 2f]. */
 tbp_status tbp_swiglu_fwd(int dtype, int rows, int f, const void* gu, void* m, void* stream);
 tbp_status tbp_swiglu_p1(int dtype, int rows, int f, const void* dm, const void* gu, void* dgu, void* stream);

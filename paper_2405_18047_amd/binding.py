@@ -11,8 +11,8 @@ import os
 import torch
 
 __all__ = [
-    "TBP_F32", "TBP_BF16", "TBP_P2_LOOP", "TBP_P2_KCONCAT", "TBP_ATTN_AUTO", "TBP_ATTN_MATERIALISED", "TBP_ATTN_FUSED", "NN", "NT", "TN", "TbpError", "lib", "library_path",
-    "tbp_config", "tbp_stash_query", "Stage", "tbp_gemm", "tbp_rmsnorm_fwd", "tbp_rmsnorm_p1", "tbp_swiglu_fwd",
+    "TBP_F32", "TBP_BF16", "TBP_P2_LOOP", "TBP_P2_KCONCAT", "TBP_ATTN_AUTO", "TBP_ATTN_MATERIALISED", "TBP_ATTN_FUSED", "TBP_GAIN_PARTIALS", "TBP_GAIN_LITERAL", "NN", "NT", "TN", "TbpError", "lib", "library_path",
+    "tbp_config", "tbp_stash_query", "Stage", "tbp_gemm", "tbp_rmsnorm_fwd", "tbp_rmsnorm_p1", "tbp_rmsnorm_gain_p2", "tbp_swiglu_fwd",
     "tbp_swiglu_p1", "tbp_rope_table", "tbp_rope", "tbp_softmax_fwd", "tbp_softmax_p1", "tbp_version",
     "tbp_attention_fwd", "tbp_attention_p1",
     "config_from_shape",
@@ -21,6 +21,7 @@ __all__ = [
 TBP_F32, TBP_BF16 = 0, 1
 TBP_P2_LOOP, TBP_P2_KCONCAT = 0, 1
 TBP_ATTN_AUTO, TBP_ATTN_MATERIALISED, TBP_ATTN_FUSED = 0, 1, 2
+TBP_GAIN_PARTIALS, TBP_GAIN_LITERAL = 0, 1
 NN, NT, TN = 0, 1, 2
 _STATUS = {0: "TBP_OK", 1: "TBP_EINVAL", 2: "TBP_ESTATE", 3: "TBP_ENOMEM", 4: "TBP_EDEVICE"}
 
@@ -34,7 +35,7 @@ class TbpError(RuntimeError):
 class tbp_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "seq", "micro_batch",
                                         "max_microbatches", "act_slots", "causal", "dtype")] + \
-               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("attention", C.c_int32)]
+               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("attention", C.c_int32), ("gain_grad", C.c_int32)]
 
 
 class _tbp_params(C.Structure):
@@ -96,6 +97,7 @@ def lib() -> C.CDLL:
         L.tbp_attention_p1.argtypes = [C.c_int] * 6 + [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.tbp_attention_fwd.argtypes = [C.c_int] * 6 + [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.tbp_rmsnorm_p1_scratch_bytes.argtypes = [C.c_int]
+        L.tbp_rmsnorm_gain_p2.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 3
         L.tbp_rope_table_bytes.argtypes = [C.c_int, C.c_int]
         _lib = L
     return _lib
@@ -127,13 +129,13 @@ def _ptr(t):
 
 
 def config_from_shape(shape, act_slots: int = 0, max_microbatches: int | None = None,
-                      attention: int = TBP_ATTN_AUTO) -> tbp_config:
+                      attention: int = TBP_ATTN_AUTO, gain_grad: int = TBP_GAIN_PARTIALS) -> tbp_config:
     """tbp_config for a seeded_inputs.StageShape-like object (any object with the same field names)."""
     return tbp_config(n_layers=shape.n_layers, d_model=shape.d_model, n_heads=shape.n_heads, head_dim=shape.head_dim,
                       d_ffn=shape.d_ffn, seq=shape.seq, micro_batch=shape.micro_batch,
                       max_microbatches=max_microbatches or shape.n_microbatches, act_slots=act_slots,
                       causal=1 if shape.causal else 0, dtype=TBP_BF16 if shape.dtype == "bf16" else TBP_F32,
-                      rms_eps=shape.rms_eps, rope_base=shape.rope_base, attention=attention)
+                      rms_eps=shape.rms_eps, rope_base=shape.rope_base, attention=attention, gain_grad=gain_grad)
 
 
 def tbp_stash_query(cfg: tbp_config) -> dict:
@@ -259,6 +261,18 @@ def tbp_rmsnorm_p1(dy, x, g, eps, resid=None):
     _check(lib().tbp_rmsnorm_p1(_dt(x), rows, d, eps, _ptr(dy), _ptr(x), _ptr(g), _ptr(resid), _ptr(dx), _ptr(dg),
                                 _ptr(scratch), _stream()))
     return dx, dg
+
+
+def tbp_rmsnorm_gain_p2(dy, x, eps, dg=None):
+    """dg (new, or += into the given fp32 vector) = sum over rows of dy * x * rsqrt(mean(x^2) + eps)."""
+    rows, d = x.shape
+    accumulate = dg is not None
+    if dg is None:
+        dg = torch.empty(d, dtype=torch.float32, device=x.device)
+    scratch = torch.empty(lib().tbp_rmsnorm_p1_scratch_bytes(d), dtype=torch.uint8, device=x.device)
+    _check(lib().tbp_rmsnorm_gain_p2(_dt(x), rows, d, eps, _ptr(dy), _ptr(x), 1 if accumulate else 0, _ptr(dg),
+                                     _ptr(scratch), _stream()))
+    return dg
 
 
 def tbp_swiglu_fwd(gu):

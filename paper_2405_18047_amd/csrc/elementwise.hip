@@ -126,7 +126,9 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(int rows, int d, float
 // LDS, with one barrier per row.  Column partials of the gain gradient stay in registers over the rows a group
 // sees and are folded over the groups through LDS in group order (fixed order: reproducible) into one partial row
 // per workgroup, which colsum_kernel adds up.
-template <typename T, int MAXC, int WPR>
+// GAIN_ONLY (the gain gradient as a backward-p2 operation): only x and dy are read, and only the partials written.
+// partials == nullptr (backward-p1 of a stage that computes the gain gradient in p2): nothing is written for the gain.
+template <typename T, int MAXC, int WPR, bool GAIN_ONLY = false>
 __global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float eps, const T* __restrict__ dy,
                                                          const T* __restrict__ x, const T* __restrict__ g,
                                                          const T* __restrict__ resid, T* __restrict__ dx,
@@ -158,7 +160,7 @@ __global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float 
         if (ch < nchunk) {
           xn[c] = Vec<T>::load_raw(x + base + ch * N);
           yn[c] = Vec<T>::load_raw(dy + base + ch * N);
-          if (resid) rn[c] = Vec<T>::load_raw(resid + base + ch * N);
+          if (!GAIN_ONLY && resid) rn[c] = Vec<T>::load_raw(resid + base + ch * N);
         }
       }
     }
@@ -184,16 +186,16 @@ __global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float 
         float xv[N], yv[N], gv[N];
         Vec<T>::unpack(xr[c], xv);
         Vec<T>::unpack(yr[c], yv);
-        Vec<T>::load(gp + ch * N, gv);
+        if constexpr (!GAIN_ONLY) Vec<T>::load(gp + ch * N, gv);
 #pragma unroll
         for (int i = 0; i < N; i++) {
           s_xx += xv[i] * xv[i];
-          s_yx += yv[i] * gv[i] * xv[i];
+          if constexpr (!GAIN_ONLY) s_yx += yv[i] * gv[i] * xv[i];
         }
       }
     }
     s_xx = wave_sum(s_xx);
-    s_yx = wave_sum(s_yx);
+    if constexpr (!GAIN_ONLY) s_yx = wave_sum(s_yx);
     if constexpr (WPR > 1) {                  // two slot sets used alternately: one barrier per row is enough
       float* const slot = red + (it & 1) * 16;
       if ((threadIdx.x & 63) == 0) {
@@ -214,24 +216,27 @@ __global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float 
     for (int c = 0; c < MAXC; c++) {
       const int ch = t + TPR * c;
       if (live && ch < nchunk) {
-        float xv[N], yv[N], gv[N], o[N];
+        float xv[N], yv[N];
         Vec<T>::unpack(xr[c], xv);
         Vec<T>::unpack(yr[c], yv);
-        Vec<T>::load(gp + ch * N, gv);
-        if (resid) Vec<T>::unpack(rr[c], o);
-        else {
 #pragma unroll
-          for (int i = 0; i < N; i++) o[i] = 0.f;
-        }
+        for (int i = 0; i < N; i++) cacc[c][i] += yv[i] * xv[i] * r;
+        if constexpr (!GAIN_ONLY) {
+          float gv[N], o[N];
+          Vec<T>::load(gp + ch * N, gv);
+          if (resid) Vec<T>::unpack(rr[c], o);
+          else {
 #pragma unroll
-        for (int i = 0; i < N; i++) {
-          o[i] += r * yv[i] * gv[i] - xv[i] * coef;
-          cacc[c][i] += yv[i] * xv[i] * r;
+            for (int i = 0; i < N; i++) o[i] = 0.f;
+          }
+#pragma unroll
+          for (int i = 0; i < N; i++) o[i] += r * yv[i] * gv[i] - xv[i] * coef;
+          Vec<T>::store(dx + base + ch * N, o);
         }
-        Vec<T>::store(dx + base + ch * N, o);
       }
     }
   }
+  if (!partials) return;                      // (uniform over the grid)
   __syncthreads();
   for (int gi = 0; gi < G; gi++) {
     if (grp == gi) {
@@ -576,7 +581,7 @@ hipError_t rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, con
   return dtype ? rmsnorm_fwd_t<bf16_t>(rows, d, eps, x, g, y, s) : rmsnorm_fwd_t<float>(rows, d, eps, x, g, y, s);
 }
 
-template <typename T, int WPR>
+template <typename T, int WPR, bool GAIN_ONLY = false>
 static hipError_t rmsnorm_p1_w(int rows, int d, float eps, const T* dy, const T* x, const T* g, const T* resid, T* dx,
                                float* partials, int* nblk_out, hipStream_t s) {
   constexpr int G = 8 / WPR;
@@ -586,40 +591,56 @@ static hipError_t rmsnorm_p1_w(int rows, int d, float eps, const T* dy, const T*
   *nblk_out = nblk;
   const size_t smem = (32 + (size_t)d) * sizeof(float);
   const dim3 grid(nblk), block(512);
-  if (c <= 1) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 1, WPR>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
-  else if (c <= 2) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 2, WPR>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
-  else if (c <= 4) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 4, WPR>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
+  if (c <= 1) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 1, WPR, GAIN_ONLY>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
+  else if (c <= 2) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 2, WPR, GAIN_ONLY>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
+  else if (c <= 4) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 4, WPR, GAIN_ONLY>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
-template <typename T>
+template <typename T, bool GAIN_ONLY = false>
 static hipError_t rmsnorm_p1_t(int rows, int d, float eps, const void* dy, const void* x, const void* g,
-                               const void* resid, void* dx, float* dg_out, float* partials, hipStream_t s) {
+                               const void* resid, void* dx, int accumulate, float* dg_out, float* partials,
+                               hipStream_t s) {
   auto DY = (const T*)dy; auto X = (const T*)x; auto G = (const T*)g; auto RS = (const T*)resid; auto DX = (T*)dx;
   const int wc = (d / Vec<T>::N + 63) / 64;         // vectors per lane if one wave owned a whole row
   int nblk = 0;
   hipError_t e;
-  if (wc <= 4) e = rmsnorm_p1_w<T, 1>(rows, d, eps, DY, X, G, RS, DX, partials, &nblk, s);
-  else if (wc <= 8) e = rmsnorm_p1_w<T, 2>(rows, d, eps, DY, X, G, RS, DX, partials, &nblk, s);
-  else if (wc <= 16) e = rmsnorm_p1_w<T, 4>(rows, d, eps, DY, X, G, RS, DX, partials, &nblk, s);
-  else e = rmsnorm_p1_w<T, 8>(rows, d, eps, DY, X, G, RS, DX, partials, &nblk, s);
-  if (e != hipSuccess) return e;
+  float* const parts = dg_out ? partials : nullptr;
+  if (wc <= 4) e = rmsnorm_p1_w<T, 1, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, parts, &nblk, s);
+  else if (wc <= 8) e = rmsnorm_p1_w<T, 2, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, parts, &nblk, s);
+  else if (wc <= 16) e = rmsnorm_p1_w<T, 4, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, parts, &nblk, s);
+  else e = rmsnorm_p1_w<T, 8, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, parts, &nblk, s);
+  if (e != hipSuccess || !dg_out) return e;
   RowList rl{};
-  hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, (const float*)partials, rl, nblk, d, 0,
-                     dg_out);
+  hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, (const float*)partials, rl, nblk, d,
+                     accumulate, dg_out);
   return hipGetLastError();
 }
 hipError_t rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
                       const void* resid, void* dx, float* dg_out, float* partials, hipStream_t s) {
   if (rows <= 0) {      // no rows: the gain gradient is zero (written by the same column-sum kernel)
+    if (!dg_out) return hipSuccess;
     RowList none{};
     hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, (const float*)partials, none, 0, d, 0,
                        dg_out);
     return hipGetLastError();
   }
-  return dtype ? rmsnorm_p1_t<bf16_t>(rows, d, eps, dy, x, g, resid, dx, dg_out, partials, s)
-               : rmsnorm_p1_t<float>(rows, d, eps, dy, x, g, resid, dx, dg_out, partials, s);
+  return dtype ? rmsnorm_p1_t<bf16_t>(rows, d, eps, dy, x, g, resid, dx, 0, dg_out, partials, s)
+               : rmsnorm_p1_t<float>(rows, d, eps, dy, x, g, resid, dx, 0, dg_out, partials, s);
+}
+
+hipError_t rmsnorm_gain_p2(int dtype, int rows, int d, float eps, const void* dy, const void* x, int accumulate,
+                           float* dg_out, float* partials, hipStream_t s) {
+  if (rows <= 0) {
+    if (accumulate) return hipSuccess;
+    RowList none{};
+    hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, (const float*)partials, none, 0, d, 0,
+                       dg_out);
+    return hipGetLastError();
+  }
+  return dtype ? rmsnorm_p1_t<bf16_t, true>(rows, d, eps, dy, x, nullptr, nullptr, nullptr, accumulate, dg_out, partials, s)
+               : rmsnorm_p1_t<float, true>(rows, d, eps, dy, x, nullptr, nullptr, nullptr, accumulate, dg_out, partials, s);
 }
 
 hipError_t gain_grad_sum(const float* parts, const int* rows_host, int n, int d, int accumulate, float* out,

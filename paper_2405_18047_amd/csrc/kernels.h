@@ -74,6 +74,9 @@ hipError_t rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, con
 constexpr int kNormPartialBlocks = 256;     // row-block partials of the gain gradient
 hipError_t rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
                       const void* resid, void* dx, float* dg_out, float* partials, hipStream_t s);
+// dg_out == nullptr in rmsnorm_p1: nothing is computed for the gain.
+hipError_t rmsnorm_gain_p2(int dtype, int rows, int d, float eps, const void* dy, const void* x, int accumulate,
+                           float* dg_out, float* partials, hipStream_t s);
 hipError_t swiglu_fwd(int dtype, int rows, int f, const void* gu, void* m, hipStream_t s);
 hipError_t swiglu_p1(int dtype, int rows, int f, const void* dm, const void* gu, void* dgu, hipStream_t s);
 hipError_t rope_table(int seq, int head_dim, float base, float2* table, hipStream_t s);

@@ -35,7 +35,9 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // consecutive micro-batches is already the batch-concatenated operand of one weight-gradient product.
 // Tensors needed only from forward to backward-p1 ("A" class) live in per-slot buffers handed out by a small
 // free list; a slot is taken at forward and returned at the end of backward-p1.
-enum WTensor { W_H1, W_A, W_H2, W_M, W_DQKV, W_DX1, W_DGU, W_DX2, W_COUNT };
+// W_N1X .. W_N2DY exist only with the literal gain-gradient p2: the inputs of the two RMSNorms and the derivatives of
+// their outputs, kept until p2 like a linear layer's operands.
+enum WTensor { W_H1, W_A, W_H2, W_M, W_N1X, W_N2X, W_DQKV, W_DX1, W_DGU, W_DX2, W_N1DY, W_N2DY, W_COUNT };
 enum ATensor { A_X0, A_QKV, A_P, A_LSE, A_X1, A_GU, A_COUNT };
 
 struct Dims {
@@ -43,6 +45,7 @@ struct Dims {
   size_t e;       // bytes per stored element
   bool attn;
   bool fused;     // attention without stored probabilities (row log-sum-exp only)
+  bool literal;   // RMSNorm gain gradients computed in p2 from stashed (x, dy) instead of p1's per-micro-batch partials
   float eps, base;
 };
 
@@ -53,18 +56,20 @@ size_t w_width(const Dims& c, int t) {
     case W_H2: case W_DX2: return c.d;
     case W_M: return c.f;
     case W_DGU: return 2 * (size_t)c.f;
+    case W_N1X: case W_N1DY: return (c.literal && c.attn) ? c.d : 0;
+    case W_N2X: case W_N2DY: return c.literal ? c.d : 0;
   }
   return 0;
 }
-bool w_from_forward(int t) { return t == W_H1 || t == W_A || t == W_H2 || t == W_M; }
+bool w_from_forward(int t) { return t == W_H1 || t == W_A || t == W_H2 || t == W_M || t == W_N1X || t == W_N2X; }
 
 size_t a_bytes(const Dims& c, int t) {      // bytes per slot
   switch (t) {
-    case A_X0: return c.attn ? (size_t)c.T * c.d * c.e : 0;
+    case A_X0: return (c.attn && !c.literal) ? (size_t)c.T * c.d * c.e : 0;     // (literal gain p2: lives in the W class)
     case A_QKV: return c.attn ? (size_t)c.T * 3 * c.d * c.e : 0;
     case A_P: return (c.attn && !c.fused) ? (size_t)c.B * c.H * c.S * c.S * c.e : 0;
     case A_LSE: return (c.attn && c.fused) ? (size_t)c.B * c.H * c.S * sizeof(float) : 0;
-    case A_X1: return (size_t)c.T * c.d * c.e;
+    case A_X1: return c.literal ? 0 : (size_t)c.T * c.d * c.e;
     case A_GU: return (size_t)c.T * 2 * c.f * c.e;
   }
   return 0;
@@ -79,7 +84,7 @@ struct Layout {
   size_t gain_part_bytes;
   size_t w_total, a_base, a_total, ws_base, ws_total, arena;
   // workspace pieces
-  size_t ws_t_f, ws_t_d0, ws_t_d1, ws_scores, ws_norm_partials, ws_rope, ws_delta;
+  size_t ws_t_f, ws_t_d0, ws_t_d1, ws_scores, ws_norm_partials, ws_norm_partials_p2, ws_rope, ws_delta;
   // accounting units
   size_t w_fwd_bytes_per_mb, w_p1_bytes_per_mb, a_bytes_per_mb;
 };
@@ -93,7 +98,7 @@ Layout plan(const Dims& c) {
   }
   y.w_layer_bytes = off;
   y.gain_part_off = y.w_layer_bytes * c.L;
-  y.gain_part_bytes = align_up((size_t)c.L * 2 * c.Mmax * c.d * sizeof(float), 256);
+  y.gain_part_bytes = c.literal ? 0 : align_up((size_t)c.L * 2 * c.Mmax * c.d * sizeof(float), 256);
   y.w_total = y.gain_part_off + y.gain_part_bytes;
   off = 0;
   for (int t = 0; t < A_COUNT; t++) {
@@ -111,6 +116,7 @@ Layout plan(const Dims& c) {
   // fp32 scores, then dS (materialised attention) or dS^T in the storage type (fused)
   y.ws_scores = off; off += c.attn ? align_up((size_t)c.B * c.H * c.S * c.S * (c.fused ? c.e : sizeof(float)), 256) : 0;
   y.ws_norm_partials = off; off += align_up((size_t)tbp::kNormPartialBlocks * c.d * sizeof(float), 256);
+  y.ws_norm_partials_p2 = off; off += c.literal ? align_up((size_t)tbp::kNormPartialBlocks * c.d * sizeof(float), 256) : 0;
   y.ws_rope = off; off += c.attn ? align_up((size_t)c.S * (c.dh / 2) * sizeof(float2), 256) : 0;
   y.ws_delta = off; off += c.attn ? align_up((size_t)c.T * c.H * sizeof(float), 256) : 0;
   y.ws_total = off;
@@ -121,7 +127,7 @@ Layout plan(const Dims& c) {
     if (w_from_forward(t)) fw += b; else p1 += b;
   }
   y.w_fwd_bytes_per_mb = fw * c.L;
-  y.w_p1_bytes_per_mb = (p1 + (c.attn ? 2 : 1) * (size_t)c.d * sizeof(float)) * c.L;
+  y.w_p1_bytes_per_mb = (p1 + (c.literal ? 0 : (c.attn ? 2 : 1) * (size_t)c.d * sizeof(float))) * c.L;
   size_t a = 0;
   for (int t = 0; t < A_COUNT; t++) a += a_bytes(c, t);
   y.a_bytes_per_mb = a * c.L;
@@ -159,6 +165,8 @@ tbp_status check_config(const tbp_config* cfg, Dims* out) {
       return fail(TBP_EINVAL, "fused attention needs bf16 storage and head_dim 64 or 128");
     c.fused = can_fuse && cfg->attention != TBP_ATTN_MATERIALISED;
   }
+  if (cfg->gain_grad != TBP_GAIN_PARTIALS && cfg->gain_grad != TBP_GAIN_LITERAL) return fail(TBP_EINVAL, "gain_grad must be a tbp_gain_grad value");
+  c.literal = cfg->gain_grad == TBP_GAIN_LITERAL;
   if (!(c.eps >= 0.f)) return fail(TBP_EINVAL, "rms_eps must be >= 0");
   if ((long)c.S * c.B > (1L << 24)) return fail(TBP_EINVAL, "tokens per micro-batch above 2^24");
   c.T = c.S * c.B;
@@ -192,6 +200,9 @@ struct tbp_stage {
     return reinterpret_cast<float*>(arena + y.gain_part_off) + ((size_t)layer * 2 + which) * c.Mmax * c.d;
   }
   void* ws(size_t off) const { return arena + y.ws_base + off; }
+  // inputs of the two RMSNorms of a layer: forward->p1 slot, or a slab kept until p2 (literal gain gradient)
+  void* x0_of(int layer, int mb, int slot) const { return c.literal ? wslab(layer, W_N1X, mb) : aslot(layer, A_X0, slot); }
+  void* x1_of(int layer, int mb, int slot) const { return c.literal ? wslab(layer, W_N2X, mb) : aslot(layer, A_X1, slot); }
   void bump() { if (w_live + a_live > high) high = w_live + a_live; }
 };
 
@@ -218,9 +229,9 @@ tbp_status run_forward(tbp_stage* st, int mb, int slot, const void* x_in, void* 
   }
   const void* x_cur = x_in;
   for (int l = 0; l < c.L; l++) {
-    void* x1 = st->aslot(l, A_X1, slot);
+    void* x1 = st->x1_of(l, mb, slot);
     if (c.attn) {
-      void* x0 = st->aslot(l, A_X0, slot);
+      void* x0 = st->x0_of(l, mb, slot);
       // the layer input is kept for the RMSNorm backward; for layer 0 it is copied from the caller
       if (l == 0) TBP_HIP(hipMemcpyAsync(x0, x_in, act_bytes, hipMemcpyDeviceToDevice, s));
       (void)x_cur;
@@ -269,7 +280,7 @@ tbp_status run_forward(tbp_stage* st, int mb, int slot, const void* x_in, void* 
     TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NN, T, 2 * f, d, h2, d, st->w_gu[l], 2 * f, gu, 2 * f), s));
     TBP_HIP(tbp::swiglu_fwd(dt, T, f, gu, m, s));
     {  // x2 = x1 + m Wd, written where the next layer (or the caller) wants its input
-      void* dst = (l + 1 < c.L) ? st->aslot(l + 1, c.attn ? A_X0 : A_X1, slot) : x_out;
+      void* dst = (l + 1 < c.L) ? (c.attn ? st->x0_of(l + 1, mb, slot) : st->x1_of(l + 1, mb, slot)) : x_out;
       GemmArgs g = gemm_args(tbp::NN, T, d, f, m, f, st->w_d[l], d, dst, d);
       g.R = x1;
       TBP_HIP(tbp::gemm(dt, g, s));
@@ -289,9 +300,10 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
     void* dx2 = st->wslab(l, W_DX2, mb);
     void* dm = st->ws(st->y.ws_t_f);
     void* dgu = st->wslab(l, W_DGU, mb);
-    void* dh = st->ws(st->y.ws_t_d0);
+    // derivative of a norm's output: a temporary, or (literal gain gradient) a slab that p2 reads
+    void* dh = c.literal ? st->wslab(l, W_N2DY, mb) : st->ws(st->y.ws_t_d0);
     void* gu = st->aslot(l, A_GU, slot);
-    void* x1 = st->aslot(l, A_X1, slot);
+    void* x1 = st->x1_of(l, mb, slot);
     // where this layer's input gradient goes: previous layer's dx2 slab, or the caller
     void* dx_out = (l > 0) ? st->wslab(l - 1, W_DX2, mb) : dx;
     // dm = dx2 Wd^T
@@ -300,12 +312,13 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
     // dh2 = [dg, du] Wgu^T
     TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NT, T, d, 2 * f, dgu, 2 * f, st->w_gu[l], 2 * f, dh, d), s));
     void* dx1 = c.attn ? st->wslab(l, W_DX1, mb) : dx_out;
-    TBP_HIP(tbp::rmsnorm_p1(dt, T, d, c.eps, dh, x1, st->g2[l], dx2, dx1, st->gain_part(l, 1) + (size_t)mb * d, npart, s));
+    TBP_HIP(tbp::rmsnorm_p1(dt, T, d, c.eps, dh, x1, st->g2[l], dx2, dx1,
+                            c.literal ? nullptr : st->gain_part(l, 1) + (size_t)mb * d, npart, s));
     if (!c.attn) continue;
     void* da = st->ws(st->y.ws_t_d1);
     void* qkv = st->aslot(l, A_QKV, slot);
     void* P = st->aslot(l, A_P, slot);
-    void* x0 = st->aslot(l, A_X0, slot);
+    void* x0 = st->x0_of(l, mb, slot);
     void* dqkv = st->wslab(l, W_DQKV, mb);
     void* dP = st->ws(st->y.ws_scores);       // dS, storage type, reuses the score workspace
     const float scale = 1.f / sqrtf((float)c.dh);
@@ -360,8 +373,10 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
     }
     TBP_HIP(tbp::rope(dt, T, c.S, 2 * c.H, c.dh, 3 * d, (const float2*)st->ws(st->y.ws_rope), 1, dqkv, s));
     // dh1 = [dq, dk, dv] Wqkv^T
-    TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NT, T, d, 3 * d, dqkv, 3 * d, st->w_qkv[l], 3 * d, dh, d), s));
-    TBP_HIP(tbp::rmsnorm_p1(dt, T, d, c.eps, dh, x0, st->g1[l], dx1, dx_out, st->gain_part(l, 0) + (size_t)mb * d, npart, s));
+    void* dh1 = c.literal ? st->wslab(l, W_N1DY, mb) : dh;
+    TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NT, T, d, 3 * d, dqkv, 3 * d, st->w_qkv[l], 3 * d, dh1, d), s));
+    TBP_HIP(tbp::rmsnorm_p1(dt, T, d, c.eps, dh1, x0, st->g1[l], dx1, dx_out,
+                            c.literal ? nullptr : st->gain_part(l, 0) + (size_t)mb * d, npart, s));
   }
   return TBP_OK;
 }
@@ -424,6 +439,23 @@ tbp_status run_p2(tbp_stage* st, const int* mbs, int n, int mode, int accumulate
           }
         }
       }
+  }
+  if (c.literal) {
+    // gain gradients from the stashed norm inputs and output derivatives (Section 3.1 treats a norm's gain like any
+    // other parameter: its gradient belongs to backward-p2); rows of consecutive micro-batches are one operand
+    float* part = (float*)st->ws(st->y.ws_norm_partials_p2);
+    const int runs = mode == TBP_P2_KCONCAT ? 1 : n;
+    const int rows = mode == TBP_P2_KCONCAT ? n * c.T : c.T;
+    for (int l = 0; l < c.L; l++)
+      for (int i = 0; i < runs; i++) {
+        const int acc = (accumulate || i > 0) ? 1 : 0;
+        if (c.attn)
+          TBP_HIP(tbp::rmsnorm_gain_p2(c.dtype, rows, c.d, c.eps, st->wslab(l, W_N1DY, mbs[i]), st->wslab(l, W_N1X, mbs[i]),
+                                       acc, st->dg1[l], part, s));
+        TBP_HIP(tbp::rmsnorm_gain_p2(c.dtype, rows, c.d, c.eps, st->wslab(l, W_N2DY, mbs[i]), st->wslab(l, W_N2X, mbs[i]),
+                                     acc, st->dg2[l], part, s));
+      }
+    return TBP_OK;
   }
   for (int l = 0; l < c.L; l++) {
     if (c.attn) TBP_HIP(tbp::gain_grad_sum(st->gain_part(l, 0), mbs, n, c.d, accumulate, st->dg1[l], s));
@@ -672,6 +704,16 @@ tbp_status tbp_rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy,
   if (rows < 0 || d < 1 || d % vecq(dtype) || d > tbp::max_d_model(dtype)) return fail(TBP_EINVAL, "bad rows / d");
   if (!g || !dg_out || !scratch || (rows > 0 && (!dy || !x || !dx))) return fail(TBP_EINVAL, "null pointer");
   TBP_HIP(tbp::rmsnorm_p1(dtype, rows, d, eps, dy, x, g, resid, dx, dg_out, (float*)scratch, static_cast<hipStream_t>(stream)));
+  return TBP_OK;
+}
+
+tbp_status tbp_rmsnorm_gain_p2(int dtype, int rows, int d, float eps, const void* dy, const void* x, int accumulate,
+                               float* dg_out, void* scratch, void* stream) {
+  if (check_dtype(dtype) != TBP_OK) return TBP_EINVAL;
+  if (rows < 0 || d < 1 || d % vecq(dtype) || d > tbp::max_d_model(dtype)) return fail(TBP_EINVAL, "bad rows / d");
+  if (!dg_out || !scratch || (rows > 0 && (!dy || !x))) return fail(TBP_EINVAL, "null pointer");
+  TBP_HIP(tbp::rmsnorm_gain_p2(dtype, rows, d, eps, dy, x, accumulate ? 1 : 0, dg_out, (float*)scratch,
+                               static_cast<hipStream_t>(stream)));
   return TBP_OK;
 }
 

@@ -220,8 +220,9 @@ def _stage_inputs(shape):
     return params, xs, dys
 
 
-def _run_gpu(shape, params, xs, dys, mode=tbp.TBP_P2_LOOP, accumulate=True, p1_order=None, attention=tbp.TBP_ATTN_AUTO):
-    st = make_gpu_stage(shape, params, attention=attention)
+def _run_gpu(shape, params, xs, dys, mode=tbp.TBP_P2_LOOP, accumulate=True, p1_order=None, attention=tbp.TBP_ATTN_AUTO,
+             gain_grad=tbp.TBP_GAIN_PARTIALS):
+    st = make_gpu_stage(shape, params, attention=attention, gain_grad=gain_grad)
     n = len(xs)
     outs = [st.forward(m, to_dev(xs[m], shape.dtype)) for m in range(n)]
     dxs = [None] * n
@@ -261,6 +262,50 @@ def test_stage_matches_oracle(name, attention, mode):
     stats = st.stats()
     assert stats["w_live_bytes"] == 0 and stats["a_live_bytes"] == 0 and stats["high_water_bytes"] > 0
     st.close()
+
+
+@pytest.mark.parametrize("name", ["tiny_f32", "ragged_f32", "small_bf16", "mlp_small_bf16", "tiles_bf16"])
+@pytest.mark.parametrize("mode", [tbp.TBP_P2_LOOP, tbp.TBP_P2_KCONCAT])
+def test_stage_with_gain_gradients_in_p2_matches_oracle(name, mode):
+    """The RMSNorm gain gradients computed in backward-p2 from stashed (x, dy) (Section 3.1 taken literally): same
+    outputs and gradients; p1 leaves no gain partials and the norm operands are released by p2."""
+    shape = SMALL[name]
+    _say(f"stage (literal gain p2) {name} mode={mode} shape={shape}")
+    params, xs, dys = _stage_inputs(shape)
+    outs, dxs, grads = run_oracle(shape, params, xs, dys)
+    st, g_outs, g_dxs = _run_gpu(shape, params, xs, dys, mode=mode, accumulate=False,
+                                 p1_order=list(reversed(range(len(xs)))), gain_grad=tbp.TBP_GAIN_LITERAL)
+    compare_stage(shape, g_outs, g_dxs, st.grads, outs, dxs, grads, stage_tolerance(shape.dtype), f"{name}/{mode}/literal")
+    stats = st.stats()
+    assert stats["w_live_bytes"] == 0 and stats["a_live_bytes"] == 0 and stats["high_water_bytes"] > 0
+    # a second set on top of the first: accumulation doubles every gradient
+    for m in range(len(xs)):
+        st.forward(m, to_dev(xs[m], shape.dtype))
+    for m in range(len(xs)):
+        st.backward_p1(m, to_dev(dys[m], shape.dtype))
+    st.backward_p2(range(len(xs)), mode=mode, accumulate=True)
+    torch.cuda.synchronize()
+    twice = {k: [2.0 * g for g in v] for k, v in grads.items()}
+    compare_stage(shape, g_outs, g_dxs, st.grads, outs, dxs, twice, stage_tolerance(shape.dtype), f"{name}/{mode}/literal x2")
+    st.close()
+
+
+@pytest.mark.parametrize("dtype,rows,d", [("f32", 0, 64), ("f32", 1, 4), ("f32", 37, 72), ("f32", 1030, 4096),
+                                          ("bf16", 1, 8), ("bf16", 300, 520), ("bf16", 1030, 4096), ("bf16", 64, 8192)])
+def test_rmsnorm_gain_p2(dtype, rows, d):
+    """dg = sum_t dy x r as its own backward-p2 operation, overwriting and accumulating."""
+    _say(f"rmsnorm_gain_p2 {dtype} rows={rows} d={d}")
+    x = _rnd(21, "x", (rows, d), dtype, 1.5)
+    dy = _rnd(21, "dy", (rows, d), dtype)
+    eps = 1e-5
+    want = ops.rmsnorm_p2(dy.astype(np.float64), x.astype(np.float64), eps)
+    got = tbp.tbp_rmsnorm_gain_p2(to_dev(dy, dtype), to_dev(x, dtype), eps)
+    if rows == 0:
+        assert float(got.abs().max()) == 0.0
+        return
+    assert max_rel(to_np(got), want) < 2e-5
+    again = tbp.tbp_rmsnorm_gain_p2(to_dev(dy, dtype), to_dev(x, dtype), eps, dg=got.clone())
+    assert max_rel(to_np(again), 2.0 * want) < 2e-5
 
 
 def test_p2_on_a_second_stream_overlapping_the_next_p1():

@@ -47,6 +47,13 @@ def test_stash_sizes_follow_the_stash_rule():
             assert fused["a_stash_bytes"] == L * M * T * ((5 * d + 2 * f) * 2 + s.n_heads * 4)
             assert fused["w_stash_bytes"] == got["w_stash_bytes"]
             assert _sizes(s)["a_stash_bytes"] == fused["a_stash_bytes"]       # AUTO picks it for bf16, head_dim 128
+        # gain gradients computed in p2: each norm's input moves from the forward->p1 slots to slabs kept until p2 and
+        # the derivative of its output is kept as well; the fp32 partials disappear
+        lit = _sizes(s, gain_grad=tbp.TBP_GAIN_LITERAL)
+        n_norms = 2 if s.n_heads else 1
+        assert lit["a_stash_bytes"] == _sizes(s)["a_stash_bytes"] - L * M * T * n_norms * d * 2
+        w_lit = L * M * T * (w_el + 2 * n_norms * d) * 2
+        assert w_lit <= lit["w_stash_bytes"] <= w_lit * 1.001 + 4096 * L
     # fewer activation slots shrink only the forward->p1 part
     s = si.CONFIGS["llama7b_s1024"]
     assert _sizes(s, act_slots=1)["a_stash_bytes"] * 4 == _sizes(s)["a_stash_bytes"]
@@ -56,7 +63,8 @@ def test_stash_sizes_follow_the_stash_rule():
 
 
 @pytest.mark.parametrize("field,value", [("d_model", 4100), ("d_ffn", 11004), ("seq", 4104), ("head_dim", 120),
-                                         ("n_layers", 0), ("dtype", 7), ("d_model", 16384), ("seq", 8192), ("attention", 3)])
+                                         ("n_layers", 0), ("dtype", 7), ("d_model", 16384), ("seq", 8192), ("attention", 3),
+                                         ("gain_grad", 2)])
 def test_bad_configs_are_rejected(field, value):
     cfg = tbp.config_from_shape(si.CONFIGS["llama7b_s1024"])
     setattr(cfg, field, value)
