@@ -218,7 +218,9 @@ tbp_status tbp_attention_p1(int dtype, int batch, int n_heads, int seq, int head
 
 /* Measurement aid (no paper passage: it prices the hardware, not the method): a register-resident loop of
  * 32x32x16 bf16 MFMAs, blocks x 4 wavefronts x iters x 16 instructions = blocks*iters*2^21 FLOP, touching no memory
- * inside the loop.  What it sustains is the practical ceiling of the matrix pipes under the chip's power management.
+ * inside the loop.  What it sustains is the practical ceiling of the matrix pipes under the chip's power management,
+ * which depends on the operand values (all-zero operands run about 1.4 times as fast as N(0,1) operands): seed it
+ * with data like the workload's.
  * seed: device, 4096 bf16 values (any finite data); sink: device, blocks*256 floats (written once). */
 tbp_status tbp_mfma_ceiling(int blocks, int iters, const void* seed, float* sink, void* stream);
 
