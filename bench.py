@@ -60,6 +60,8 @@ def main() -> int:
                     help="skip the extra loop-mode p2 steps (profiles: every dW launch is then a K-concatenated one)")
     ap.add_argument("--no-call-orders", action="store_true",
                     help="skip the extra passes that time other call orders (p2 interleaved with p1, partial flushes)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the other benchmark configurations")
     ap.add_argument("--probe", action="store_true",
                     help="for hardware-counter runs: one forward/p1 pass, then a plain 1 GiB device copy (calibration) "
                          "and two K-concatenated p2 passes; prints nothing but a marker line")
@@ -207,11 +209,58 @@ def main() -> int:
             if "us" in v:
                 v["frac_of_device_copy"] = round(v["GB/s"] / copy_ref, 4)
     st.close()
-    del st
+    del st, params, xs, dys
+    if not args.no_other_workloads:
+        # the benchmark definition's other configurations, each as a short run of the same step (context beside the
+        # headline workload: they are parity-test cases first)
+        torch.cuda.empty_cache()
+        out["other_workloads"] = {n: other_workload(si.CONFIGS[n], tbp, torch, dev)
+                                  for n in si.CONFIGS if n != shape.name}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def other_workload(shape, tbp, torch, dev, steps=3) -> dict:
+    """One warm-up and `steps` timed passes of forward (all micro-batches), p1 (each), K-concatenated p2 on a stage of
+    the given configuration with synthetic N(0,1) inputs; event-timed per phase."""
+    tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(shape.seed)
+    rn = lambda *size, std=1.0, mean=0.0: (torch.randn(*size, generator=gen, device=dev, dtype=torch.float32) * std + mean).to(tdt)
+    d, f, L, M = shape.d_model, shape.d_ffn, shape.n_layers, shape.n_microbatches
+    params = {"w_gu": [rn(d, 2 * f, std=0.02) for _ in range(L)], "w_d": [rn(f, d, std=0.02) for _ in range(L)],
+              "g2": [rn(d, std=0.02, mean=1.0) for _ in range(L)]}
+    if shape.n_heads:
+        params.update({"w_qkv": [rn(d, 3 * d, std=0.02) for _ in range(L)], "w_o": [rn(d, d, std=0.02) for _ in range(L)],
+                       "g1": [rn(d, std=0.02, mean=1.0) for _ in range(L)]})
+    x, dy = rn(shape.tokens, d), rn(shape.tokens, d)
+    x_out, dx_out = torch.empty_like(x), torch.empty_like(x)
+    st = tbp.Stage(tbp.config_from_shape(shape), params, dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    fwd, p1, p2 = [], [], []
+    for it in range(steps + 1):
+        e = [ev() for _ in range(4)]
+        e[0].record()
+        for m in range(M):
+            st.forward(m, x, x_out)
+        e[1].record()
+        for m in range(M):
+            st.backward_p1(m, dy, dx_out)
+        e[2].record()
+        st.backward_p2(range(M), tbp.TBP_P2_KCONCAT, accumulate=False)
+        e[3].record()
+        torch.cuda.synchronize()
+        if it:
+            fwd.append(e[0].elapsed_time(e[1]) / M); p1.append(e[1].elapsed_time(e[2]) / M); p2.append(e[2].elapsed_time(e[3]))
+    sizes = st.sizes
+    st.close()
+    p2m = statistics.median(p2)
+    return {"p2_tflops": round(p2_flops(shape) / (p2m * 1e-3) / 1e12, 2), "p2_ms": round(p2m, 3),
+            "p1_ms_per_microbatch": round(statistics.median(p1), 3), "fwd_ms_per_microbatch": round(statistics.median(fwd), 3),
+            "dtype": shape.dtype, "tokens_per_microbatch": shape.tokens, "n_microbatches": M,
+            "stash_bytes": sizes["w_stash_bytes"] + sizes["a_stash_bytes"]}
 
 
 def call_orders(st, tbp, torch, xs, dys, x_out, dx_out, M, p1_deferred_ms) -> dict:
