@@ -172,6 +172,17 @@ tbp_status tbp_stage_reset(tbp_stage* st);
 tbp_status tbp_gemm(int dtype, int layout, int M, int N, int K, float alpha, const void* A, int lda,
                     const void* B, int ldb, void* C, int ldc, int out_f32, int accumulate, const void* R,
                     void* stream);
+/* The same product with scratch memory.  A bf16 NN or NT product with a storage-type output of fewer than 192 tiles of
+ * 256 x 256 cannot fill the chip with one workgroup per tile; given `workspace` (device, 256-byte aligned, at least
+ * tbp_gemm_workspace_bytes(...) bytes) the contraction is split over several workgroups per tile whose fp32 partial
+ * sums meet in the workspace and are added in a fixed order (the result does not depend on timing).
+ * tbp_gemm_workspace_bytes returns 0 for a product that would not be split; workspace may then be NULL.  The call
+ * clears the part of the workspace it relies on; calls that share a workspace must not overlap.  The stage gives its
+ * forward and backward-p1 linear products such a workspace out of its arena (Section 3.1: dX = dY W^T). */
+size_t tbp_gemm_workspace_bytes(int dtype, int layout, int M, int N, int K, int out_f32);
+tbp_status tbp_gemm_ws(int dtype, int layout, int M, int N, int K, float alpha, const void* A, int lda,
+                       const void* B, int ldb, void* C, int ldc, int out_f32, int accumulate, const void* R,
+                       void* workspace, size_t workspace_bytes, void* stream);
 tbp_status tbp_rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, const void* g, void* y,
                            void* stream);
 /* dx = resid + dL/dx of RMSNorm (resid may be NULL); dg_out [d] fp32 = sum_t dy x r (overwritten).

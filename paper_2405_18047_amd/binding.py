@@ -74,6 +74,10 @@ def lib() -> C.CDLL:
         L.tbp_stage_destroy.restype = None
         L.tbp_gemm.argtypes = [C.c_int] * 5 + [C.c_float, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
                                                 C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.tbp_gemm_ws.argtypes = [C.c_int] * 5 + [C.c_float, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
+                                                   C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.tbp_gemm_workspace_bytes.argtypes = [C.c_int] * 6
+        L.tbp_gemm_workspace_bytes.restype = C.c_size_t
         L.tbp_rmsnorm_fwd.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float] + [C.c_void_p] * 4
         L.tbp_rmsnorm_p1.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float] + [C.c_void_p] * 8
         L.tbp_swiglu_fwd.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 3
@@ -232,7 +236,9 @@ class Stage:
 
 # ---- single operations ------------------------------------------------------------------------------
 def tbp_gemm(layout: int, A: torch.Tensor, B: torch.Tensor, *, out_f32: bool = False, alpha: float = 1.0,
-             C_out: torch.Tensor | None = None, accumulate: bool = False, R: torch.Tensor | None = None) -> torch.Tensor:
+             C_out: torch.Tensor | None = None, accumulate: bool = False, R: torch.Tensor | None = None,
+             workspace: torch.Tensor | bool | None = None) -> torch.Tensor:
+    """workspace: a uint8 device tensor for tbp_gemm_ws, or True to allocate what tbp_gemm_workspace_bytes asks for."""
     dt = _dt(A)
     if layout == TN:
         K, M = A.shape
@@ -242,8 +248,16 @@ def tbp_gemm(layout: int, A: torch.Tensor, B: torch.Tensor, *, out_f32: bool = F
     if C_out is None:
         C_out = torch.empty((M, N), dtype=torch.float32 if (out_f32 or dt == TBP_F32) else A.dtype, device=A.device)
     ld = lambda t: t.stride(0) if t.numel() > 0 else max(t.shape[-1], 8)     # empty tensors carry no usable stride
-    _check(lib().tbp_gemm(dt, layout, M, N, K, alpha, _ptr(A), ld(A), _ptr(B), ld(B), _ptr(C_out), ld(C_out),
-                          1 if C_out.dtype == torch.float32 else 0, 1 if accumulate else 0, _ptr(R), _stream()))
+    f32 = 1 if C_out.dtype == torch.float32 else 0
+    if workspace is True:
+        need = lib().tbp_gemm_workspace_bytes(dt, layout, M, N, K, f32)
+        workspace = torch.empty(need, dtype=torch.uint8, device=A.device) if need else None
+    if workspace is None or workspace is False:
+        _check(lib().tbp_gemm(dt, layout, M, N, K, alpha, _ptr(A), ld(A), _ptr(B), ld(B), _ptr(C_out), ld(C_out),
+                              f32, 1 if accumulate else 0, _ptr(R), _stream()))
+    else:
+        _check(lib().tbp_gemm_ws(dt, layout, M, N, K, alpha, _ptr(A), ld(A), _ptr(B), ld(B), _ptr(C_out), ld(C_out),
+                                 f32, 1 if accumulate else 0, _ptr(R), _ptr(workspace), workspace.numel(), _stream()))
     return C_out
 
 

@@ -32,6 +32,10 @@ struct GemmParams {
   // fused softmax backward (see GemmArgs)
   const float* delta; long ldd, sDo, sDi;
   int delta_causal;
+  // contraction split over `split` workgroups per tile (see SplitPlan)
+  int split;
+  float* split_ws;
+  unsigned* split_cnt;
 };
 
 constexpr int BK = 32;                     // contraction depth of one LDS slot
@@ -136,8 +140,9 @@ __device__ __forceinline__ bf16x8 read_frag(lds_u8* q) {
 // operands whose contraction index is contiguous in memory: their copies then fetch 128 contiguous bytes per tile
 // row, a whole cache line, where the 32-deep slot fetches every line in two halves one iteration apart and doubles
 // the number of requests to the L2.
-template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD = BK>
-__device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, int tn_i, int z) {
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD = BK, bool SPLIT = false>
+__device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, int tn_i, int z, int split_idx = 0,
+                                               int tile_seq = 0) {
   constexpr int NS = KD == 32 ? STAGES : 2;     // ring slots
   constexpr int WM = BM / 2, WN = BN / 2;       // per-wave tile
   constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wave
@@ -165,6 +170,11 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
     k_hi = (m0 + BM < p.K) ? m0 + BM : p.K;
   } else if (p.causal == CAUSAL_K_BEGIN) {
     k_lo = m0;
+  }
+  if constexpr (SPLIT) {      // this workgroup's slice of the contraction, in whole slots (may be empty)
+    const int per = ((p.K + KD - 1) / KD + p.split - 1) / p.split * KD;
+    k_lo = split_idx * per < p.K ? split_idx * per : p.K;
+    k_hi = k_lo + per < p.K ? k_lo + per : p.K;
   }
   const int nk = (k_hi - k_lo + KD - 1) / KD;
 
@@ -335,6 +345,56 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   // a lane owns single elements of many rows.  Each wave therefore passes its tile through LDS one 32-row strip at
   // a time (the ring is free by now) and reads it back row-major, so that every lane stores 16 contiguous bytes
   // and a wave-wide store covers whole rows of the tile.
+  if constexpr (SPLIT) {
+    // Partial sums meet in memory: every workgroup of a tile leaves its accumulators there in register order (lane-
+    // contiguous 16-byte stores), makes them visible and takes a ticket; the one that draws the last ticket adds all
+    // slices up in slice order, clears the counter for the next product and goes on to the epilogue.  Nobody waits
+    // for anybody: a workgroup that is not last is simply done.
+    constexpr long TILE = (long)BM * BN;
+    float* const mine = p.split_ws + ((long)tile_seq * p.split + split_idx) * TILE;
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; e4++) {
+          f32x4 v;
+#pragma unroll
+          for (int q = 0; q < 4; q++) v[q] = acc[i][j][4 * e4 + q];
+          *reinterpret_cast<f32x4*>(mine + ((((i * TN + j) * 4 + e4) * 256 + tid) << 2)) = v;
+        }
+    // All slices of a tile run on one XCD (see the launch map), so the partial sums only have to reach that XCD's L2,
+    // which stores do before the wave's memory counter lets go of them; a device-wide fence here would write back and
+    // invalidate the whole L2 under every other workgroup's operands.  The readers' vector caches cannot hold these
+    // lines: each is written once and read once per launch, and a launch starts with clean vector caches.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    LDS_AS int* const last_arrival = reinterpret_cast<LDS_AS int*>(lds);     // (the ring is free once all waves are here)
+    __syncthreads();
+    if (tid == 0) *last_arrival = atomicAdd(p.split_cnt + tile_seq, 1u) == (unsigned)(p.split - 1);
+    __syncthreads();
+    if (!*last_arrival) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+    for (int sl = 0; sl < p.split; sl++) {
+      const float* const part = p.split_ws + ((long)tile_seq * p.split + sl) * TILE;
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+#pragma unroll
+          for (int e4 = 0; e4 < 4; e4++) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(part + ((((i * TN + j) * 4 + e4) * 256 + tid) << 2));
+#pragma unroll
+            for (int q = 0; q < 4; q++) acc[i][j][4 * e4 + q] += v[q];
+          }
+    }
+    if (tid == 0) p.split_cnt[tile_seq] = 0u;
+  }
   __syncthreads();                          // every wave is done with the ring
   OutT* C = reinterpret_cast<OutT*>(p.C) + zo * p.sCo + zi * p.sCi;
   const bf16_t* R = reinterpret_cast<const bf16_t*>(p.R);
@@ -442,6 +502,28 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     }
   }
   gemm_bf16_tile<BM, BN, AKC, BKC, OutT, KD>(p, tm_i, tn_i, (int)blockIdx.z);
+}
+
+// `split` workgroups per output tile, each over its slice of the contraction.  The hardware hands consecutive
+// workgroup ids to the 8 XCDs in turn; ids that differ by 8 share an XCD, and those are made the slices of one tile, so
+// that the partial sums of a tile meet in one L2.
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD>
+__global__ __launch_bounds__(256) void gemm_bf16_splitk_kernel(GemmParams p) {
+  const int v = (int)blockIdx.x, xcd = v & 7, q = v >> 3;
+  const int split_idx = q % p.split;
+  const int tq = q / p.split;                 // which of this XCD's tiles
+  const int nt = p.tiles_m * p.tiles_n;
+  if (tq >= (nt >> 3) + (xcd < (nt & 7) ? 1 : 0)) return;
+  // the same tile order as the unsplit kernel: an XCD owns a contiguous stretch of it, i.e. a compact patch of tiles
+  int tm_i, tn_i;
+  tile_of_block(tq * 8 + xcd, p.tiles_m, p.tiles_n, tm_i, tn_i);
+  const int tile_seq = tn_i * p.tiles_m + tm_i;
+  gemm_bf16_tile<BM, BN, AKC, BKC, OutT, KD, true>(p, tm_i, tn_i, 0, split_idx, tile_seq);
+}
+
+__global__ void fill_u32_kernel(unsigned* dst, int n, unsigned value) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = value;
 }
 
 // Several independent weight-gradient products (TN layout, fp32 output) in one launch: the tiles of all products form
@@ -618,6 +700,57 @@ static hipError_t launch_bf16(const GemmParams& p0, int batch, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Cost model behind gemm_split_plan, fitted to measurements on this chip (microseconds): a round of large tiles costs
+// 0.0245 per contraction index plus 12 of prologue and epilogue; the exchange of partial sums costs about 30 plus
+// 0.67 per MiB of partials (they are written by every workgroup but read back by one workgroup per tile only); the
+// small-tile kernel that such outputs otherwise use sustains about 800 TFLOP/s.  In practice only long contractions
+// pay: e.g. [2048, 5120] x K = 27648 runs in 590 us split three ways against 810 us.
+SplitPlan gemm_split_plan(int dtype, int layout, int M, int N, int K, int out_f32, int batch) {
+  SplitPlan none{1, 0};
+  if (dtype != 1 || out_f32 || batch != 1 || layout == TN || M < 256 || N < 256) return none;
+  const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
+  if (tiles >= 192) return none;
+  double best = 2.0 * M * N * (double)K / 800e6;
+  int split = 1;
+  for (int sp = 2; sp <= 8; sp++) {
+    if (K / sp < 512) break;
+    const long rounds = (tiles * sp + 255) / 256;
+    const double t = rounds * (0.0245 * K / sp + 12.0) + 30.0 + 0.67 * (tiles * sp * 0.25);
+    if (t < 0.9 * best) { best = t; split = sp; }
+  }
+  if (split == 1) return none;
+  return SplitPlan{split, kSplitCounterBytes + (size_t)tiles * split * 256 * 256 * sizeof(float)};
+}
+
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD>
+static hipError_t launch_bf16_split(const GemmParams& p0, int split, void* ws, int counters_zero, hipStream_t s) {
+  GemmParams p = p0;
+  p.tiles_m = (p.M + BM - 1) / BM;
+  p.tiles_n = (p.N + BN - 1) / BN;
+  p.split = split;
+  p.split_cnt = static_cast<unsigned*>(ws);
+  p.split_ws = reinterpret_cast<float*>(static_cast<char*>(ws) + kSplitCounterBytes);
+  const int tiles = p.tiles_m * p.tiles_n;
+  if ((size_t)tiles * sizeof(unsigned) > kSplitCounterBytes) return hipErrorInvalidValue;
+  constexpr size_t smem = (size_t)(KD == 32 ? STAGES : 2) * (BM + BN) * KD * sizeof(bf16_t);
+  auto kern = gemm_bf16_splitk_kernel<BM, BN, AKC, BKC, OutT, KD>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  if (!counters_zero) {
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, s, p.split_cnt, (int)(kSplitCounterBytes / 4), 0u);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const unsigned blocks = (unsigned)((tiles + 7) / 8 * 8 * split);
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
 // Slot depth by layout and tile size: operands with a contiguous contraction index get the 64-deep slots on the
 // large tiles (whole cache lines per tile row: up to 8 % faster); on the small tiles, which run two or three
 // workgroups per compute unit and overlap that way, the 4-slot ring of 32-deep slots stays ahead.
@@ -692,6 +825,12 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
   // short contractions (the per-head q k^T and do v^T, K = head_dim) are all prologue and epilogue: small tiles let
   // two or three workgroups share a compute unit and overlap them
   const bool big = g.M >= 256 && g.N >= 256 && tiles_big >= 192 && g.K > 256;
+  if (g.ws && g.causal == CAUSAL_NONE && !g.delta && reinterpret_cast<uintptr_t>(g.ws) % 256 == 0) {
+    const SplitPlan plan = gemm_split_plan(dtype, g.layout, g.M, g.N, g.K, g.out_f32, g.batch);
+    if (plan.split > 1 && plan.bytes <= g.ws_bytes)
+      return g.layout == NN ? launch_bf16_split<256, 256, true, false, bf16_t, 64>(p, plan.split, g.ws, g.ws_counters_zero, s)
+                            : launch_bf16_split<256, 256, true, true, bf16_t, 64>(p, plan.split, g.ws, g.ws_counters_zero, s);
+  }
   auto run = [&](const GemmParams& q, bool use_big) -> hipError_t {
     if (g.out_f32)
       return use_big ? dispatch_layout<256, 256, float>(g.layout, q, g.batch, s)

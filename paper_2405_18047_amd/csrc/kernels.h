@@ -39,7 +39,22 @@ struct GemmArgs {
   // delta[(zo * sDo + zi * sDi) + row * ldd] = rowsum(dP * P) = sum over the head's columns of do * o.
   const float* delta; long ldd, sDo, sDi;
   int delta_causal;
+  // Optional scratch for products whose output has too few large tiles to fill the chip (see gemm_split_plan):
+  // device memory of at least gemm_split_plan(...).bytes bytes, 256-byte aligned.  Its first kSplitCounterBytes hold
+  // per-tile arrival counters that must be zero when a product starts and are zero again when it ends;
+  // ws_counters_zero = 0 makes gemm() clear them first (a small fill launch).
+  void* ws; size_t ws_bytes;
+  int ws_counters_zero;
 };
+
+// Split of the contraction over several workgroups per output tile.  An output with fewer than 192 tiles of
+// 256 x 256 leaves compute units idle (or falls back to small tiles that move twice the operand bytes per FLOP);
+// with `split` workgroups per tile, each summing a slice of the contraction into fp32 partials in the scratch buffer,
+// the chip is full again.  The workgroup that arrives last at a tile adds the partials up in slice order (so the result
+// does not depend on arrival order), and runs the ordinary epilogue.  split == 1: not worth it / not applicable.
+struct SplitPlan { int split; size_t bytes; };
+constexpr size_t kSplitCounterBytes = 1024;
+SplitPlan gemm_split_plan(int dtype, int layout, int M, int N, int K, int out_f32, int batch);
 
 inline GemmArgs gemm_args(int layout, int M, int N, int K, const void* A, long lda, const void* B, long ldb,
                           void* C, long ldc) {

@@ -3,6 +3,7 @@
 #include "../../include/tbp.h"
 #include "kernels.h"
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -84,7 +85,8 @@ struct Layout {
   size_t gain_part_bytes;
   size_t w_total, a_base, a_total, ws_base, ws_total, arena;
   // workspace pieces
-  size_t ws_t_f, ws_t_d0, ws_t_d1, ws_scores, ws_norm_partials, ws_norm_partials_p2, ws_rope, ws_delta;
+  size_t ws_t_f, ws_t_d0, ws_t_d1, ws_scores, ws_norm_partials, ws_norm_partials_p2, ws_rope, ws_delta, ws_split;
+  size_t ws_split_bytes;        // scratch of the products that split their contraction (0: none does)
   // accounting units
   size_t w_fwd_bytes_per_mb, w_p1_bytes_per_mb, a_bytes_per_mb;
 };
@@ -119,6 +121,17 @@ Layout plan(const Dims& c) {
   y.ws_norm_partials_p2 = off; off += c.literal ? align_up((size_t)tbp::kNormPartialBlocks * c.d * sizeof(float), 256) : 0;
   y.ws_rope = off; off += c.attn ? align_up((size_t)c.S * (c.dh / 2) * sizeof(float2), 256) : 0;
   y.ws_delta = off; off += c.attn ? align_up((size_t)c.T * c.H * sizeof(float), 256) : 0;
+  {  // the forward and backward-p1 products of a layer, [T, out] = [T, in] x W: the largest scratch any of them wants
+    const int outs[4] = {3 * c.d, c.d, 2 * c.f, c.d}, ins[4] = {c.d, c.d, c.d, c.f};
+    size_t need = 0;
+    for (int i = 0; i < 4; i++) {
+      if (!c.attn && i < 2) continue;
+      need = std::max(need, tbp::gemm_split_plan(c.dtype, tbp::NN, c.T, outs[i], ins[i], 0, 1).bytes);
+      need = std::max(need, tbp::gemm_split_plan(c.dtype, tbp::NT, c.T, ins[i], outs[i], 0, 1).bytes);
+    }
+    y.ws_split_bytes = need;
+    y.ws_split = off; off += align_up(need, 256);
+  }
   y.ws_total = off;
   y.arena = y.ws_base + y.ws_total;
   size_t fw = 0, p1 = 0;
@@ -188,6 +201,7 @@ struct tbp_stage {
   std::vector<int> slot_of;     // per micro-batch, -1 if none
   std::vector<int> free_slots;
   bool rope_ready;
+  bool split_ready;             // the arrival counters of the split products have been cleared once
   size_t w_live, a_live, high;
 
   void* wslab(int layer, int t, int mb) const {
@@ -219,6 +233,22 @@ GemmArgs head_gemm(const Dims& c, int layout, int M, int N, int K) {
   return g;
 }
 
+// A linear-layer product of the forward or backward-p1 pass: handed the stage's scratch when its output is small
+// enough for the contraction to be split over several workgroups per tile.
+hipError_t linear_gemm(tbp_stage* st, GemmArgs g, hipStream_t s) {
+  const Dims& c = st->c;
+  if (st->y.ws_split_bytes) {
+    const tbp::SplitPlan plan = tbp::gemm_split_plan(c.dtype, g.layout, g.M, g.N, g.K, g.out_f32, g.batch);
+    if (plan.split > 1 && plan.bytes <= st->y.ws_split_bytes) {
+      g.ws = st->ws(st->y.ws_split);
+      g.ws_bytes = st->y.ws_split_bytes;
+      g.ws_counters_zero = st->split_ready ? 1 : 0;
+      st->split_ready = true;
+    }
+  }
+  return tbp::gemm(c.dtype, g, s);
+}
+
 tbp_status run_forward(tbp_stage* st, int mb, int slot, const void* x_in, void* x_out, hipStream_t s) {
   const Dims& c = st->c;
   const int dt = c.dtype, T = c.T, d = c.d, f = c.f;
@@ -240,7 +270,7 @@ tbp_status run_forward(tbp_stage* st, int mb, int slot, const void* x_in, void* 
       void* P = st->aslot(l, A_P, slot);
       void* a = st->wslab(l, W_A, mb);
       TBP_HIP(tbp::rmsnorm_fwd(dt, T, d, c.eps, x0, st->g1[l], h1, s));
-      TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NN, T, 3 * d, d, h1, d, st->w_qkv[l], 3 * d, qkv, 3 * d), s));
+      TBP_HIP(linear_gemm(st, gemm_args(tbp::NN, T, 3 * d, d, h1, d, st->w_qkv[l], 3 * d, qkv, 3 * d), s));
       TBP_HIP(tbp::rope(dt, T, c.S, 2 * c.H, c.dh, 3 * d, (const float2*)st->ws(st->y.ws_rope), 0, qkv, s));
       if (c.fused) {
         TBP_HIP(tbp::attention_fwd(c.B, c.H, c.S, c.dh, c.causal, qkv, 3 * d, a, d, (float*)st->aslot(l, A_LSE, slot), s));
@@ -268,7 +298,7 @@ tbp_status run_forward(tbp_stage* st, int mb, int slot, const void* x_in, void* 
       {  // x1 = x0 + a Wo
         GemmArgs g = gemm_args(tbp::NN, T, d, d, a, d, st->w_o[l], d, x1, d);
         g.R = x0;
-        TBP_HIP(tbp::gemm(dt, g, s));
+        TBP_HIP(linear_gemm(st, g, s));
       }
     } else if (l == 0) {
       TBP_HIP(hipMemcpyAsync(x1, x_in, act_bytes, hipMemcpyDeviceToDevice, s));
@@ -277,13 +307,13 @@ tbp_status run_forward(tbp_stage* st, int mb, int slot, const void* x_in, void* 
     void* gu = st->aslot(l, A_GU, slot);
     void* m = st->wslab(l, W_M, mb);
     TBP_HIP(tbp::rmsnorm_fwd(dt, T, d, c.eps, x1, st->g2[l], h2, s));
-    TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NN, T, 2 * f, d, h2, d, st->w_gu[l], 2 * f, gu, 2 * f), s));
+    TBP_HIP(linear_gemm(st, gemm_args(tbp::NN, T, 2 * f, d, h2, d, st->w_gu[l], 2 * f, gu, 2 * f), s));
     TBP_HIP(tbp::swiglu_fwd(dt, T, f, gu, m, s));
     {  // x2 = x1 + m Wd, written where the next layer (or the caller) wants its input
       void* dst = (l + 1 < c.L) ? (c.attn ? st->x0_of(l + 1, mb, slot) : st->x1_of(l + 1, mb, slot)) : x_out;
       GemmArgs g = gemm_args(tbp::NN, T, d, f, m, f, st->w_d[l], d, dst, d);
       g.R = x1;
-      TBP_HIP(tbp::gemm(dt, g, s));
+      TBP_HIP(linear_gemm(st, g, s));
     }
   }
   return TBP_OK;
@@ -307,10 +337,10 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
     // where this layer's input gradient goes: previous layer's dx2 slab, or the caller
     void* dx_out = (l > 0) ? st->wslab(l - 1, W_DX2, mb) : dx;
     // dm = dx2 Wd^T
-    TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NT, T, f, d, dx2, d, st->w_d[l], d, dm, f), s));
+    TBP_HIP(linear_gemm(st, gemm_args(tbp::NT, T, f, d, dx2, d, st->w_d[l], d, dm, f), s));
     TBP_HIP(tbp::swiglu_p1(dt, T, f, dm, gu, dgu, s));
     // dh2 = [dg, du] Wgu^T
-    TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NT, T, d, 2 * f, dgu, 2 * f, st->w_gu[l], 2 * f, dh, d), s));
+    TBP_HIP(linear_gemm(st, gemm_args(tbp::NT, T, d, 2 * f, dgu, 2 * f, st->w_gu[l], 2 * f, dh, d), s));
     void* dx1 = c.attn ? st->wslab(l, W_DX1, mb) : dx_out;
     TBP_HIP(tbp::rmsnorm_p1(dt, T, d, c.eps, dh, x1, st->g2[l], dx2, dx1,
                             c.literal ? nullptr : st->gain_part(l, 1) + (size_t)mb * d, npart, s));
@@ -324,7 +354,7 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
     const float scale = 1.f / sqrtf((float)c.dh);
     const long hs = (long)c.S * c.S, bs = (long)c.H * hs, tok3 = (long)c.S * 3 * d;
     // da = dx1 Wo^T
-    TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NT, T, d, d, dx1, d, st->w_o[l], d, da, d), s));
+    TBP_HIP(linear_gemm(st, gemm_args(tbp::NT, T, d, d, dx1, d, st->w_o[l], d, da, d), s));
     if (c.fused) {
       // probabilities rebuilt from the stashed row log-sum-exp; dq, dk, dv straight into the dqkv slab
       TBP_HIP(tbp::attention_p1(c.B, c.H, c.S, c.dh, c.causal, qkv, 3 * d, st->wslab(l, W_A, mb), da, d,
@@ -374,7 +404,7 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
     TBP_HIP(tbp::rope(dt, T, c.S, 2 * c.H, c.dh, 3 * d, (const float2*)st->ws(st->y.ws_rope), 1, dqkv, s));
     // dh1 = [dq, dk, dv] Wqkv^T
     void* dh1 = c.literal ? st->wslab(l, W_N1DY, mb) : dh;
-    TBP_HIP(tbp::gemm(dt, gemm_args(tbp::NT, T, d, 3 * d, dqkv, 3 * d, st->w_qkv[l], 3 * d, dh1, d), s));
+    TBP_HIP(linear_gemm(st, gemm_args(tbp::NT, T, d, 3 * d, dqkv, 3 * d, st->w_qkv[l], 3 * d, dh1, d), s));
     TBP_HIP(tbp::rmsnorm_p1(dt, T, d, c.eps, dh1, x0, st->g1[l], dx1, dx_out,
                             c.literal ? nullptr : st->gain_part(l, 0) + (size_t)mb * d, npart, s));
   }
@@ -525,6 +555,7 @@ tbp_status tbp_stage_create(const tbp_config* cfg, const tbp_params* params, voi
   st->slot_of.assign(c.Mmax, -1);
   for (int i = c.slots - 1; i >= 0; i--) st->free_slots.push_back(i);
   st->rope_ready = false;
+  st->split_ready = false;
   st->w_live = st->a_live = st->high = 0;
   *out = st;
   return TBP_OK;
@@ -612,8 +643,19 @@ static tbp_status check_dtype(int dtype) {
   return (dtype == TBP_F32 || dtype == TBP_BF16) ? TBP_OK : fail(TBP_EINVAL, "dtype must be TBP_F32 or TBP_BF16");
 }
 
+size_t tbp_gemm_workspace_bytes(int dtype, int layout, int M, int N, int K, int out_f32) {
+  if (M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 2) return 0;
+  return tbp::gemm_split_plan(dtype, layout, M, N, K, out_f32, 1).bytes;
+}
+
 tbp_status tbp_gemm(int dtype, int layout, int M, int N, int K, float alpha, const void* A, int lda, const void* B,
                     int ldb, void* C, int ldc, int out_f32, int accumulate, const void* R, void* stream) {
+  return tbp_gemm_ws(dtype, layout, M, N, K, alpha, A, lda, B, ldb, C, ldc, out_f32, accumulate, R, nullptr, 0, stream);
+}
+
+tbp_status tbp_gemm_ws(int dtype, int layout, int M, int N, int K, float alpha, const void* A, int lda, const void* B,
+                       int ldb, void* C, int ldc, int out_f32, int accumulate, const void* R, void* workspace,
+                       size_t workspace_bytes, void* stream) {
   if (check_dtype(dtype) != TBP_OK) return TBP_EINVAL;
   if (layout < 0 || layout > 2) return fail(TBP_EINVAL, "layout must be 0 (NN), 1 (NT) or 2 (TN)");
   if (M < 0 || N < 0 || K < 0) return fail(TBP_EINVAL, "negative size");
@@ -633,6 +675,10 @@ tbp_status tbp_gemm(int dtype, int layout, int M, int N, int K, float alpha, con
   if (R && out_f32 && dtype == TBP_BF16) return fail(TBP_EINVAL, "residual is only added to storage-type outputs");
   tbp::GemmArgs g = gemm_args(layout, M, N, K, A, lda, B, ldb, C, ldc);
   g.alpha = alpha; g.out_f32 = out_f32; g.accumulate = accumulate; g.R = R;
+  if (workspace) {
+    if ((uintptr_t)workspace % 256) return fail(TBP_EINVAL, "workspace must be 256-byte aligned");
+    g.ws = workspace; g.ws_bytes = workspace_bytes; g.ws_counters_zero = 0;     // a caller's buffer: cleared here
+  }
   TBP_HIP(tbp::gemm(dtype, g, static_cast<hipStream_t>(stream)));
   return TBP_OK;
 }

@@ -59,6 +59,43 @@ def test_gemm_matches_definition(dtype, layout, mnk):
         assert max_rel(to_np(got), ref + R) < 4.5e-3
 
 
+@pytest.mark.parametrize("layout", [tbp.NN, tbp.NT])
+@pytest.mark.parametrize("mnk", [(1024, 4096, 32768), (1000, 4040, 32776), (2048, 5120, 27648)])
+def test_gemm_with_split_contraction(layout, mnk):
+    """bf16 products whose output is too small to fill the chip: given scratch memory, several workgroups share a tile
+    and their partial sums meet in the scratch.  Same result as the definition, identical from call to call (the
+    partials are added in a fixed order), the scratch is reusable without being cleared by the caller, and a residual
+    is still added once."""
+    M, N, K = mnk
+    dtype = "bf16"
+    _say(f"gemm split-K layout={layout} M,N,K={mnk}")
+    need = tbp.lib().tbp_gemm_workspace_bytes(tbp.TBP_BF16, layout, M, N, K, 0)
+    assert need > 0, "these shapes are meant to take the split path"
+    assert tbp.lib().tbp_gemm_workspace_bytes(tbp.TBP_BF16, tbp.TN, M, N, K, 1) == 0
+    assert tbp.lib().tbp_gemm_workspace_bytes(tbp.TBP_BF16, layout, 4096, 4096, K, 0) == 0      # 256 tiles: no split
+    assert tbp.lib().tbp_gemm_workspace_bytes(tbp.TBP_BF16, layout, M, N, 4096, 0) == 0         # short contraction: no gain
+    a_shape = (M, K)
+    b_shape = (N, K) if layout == tbp.NT else (K, N)
+    A, B = _rnd(13, "A", a_shape, dtype), _rnd(13, "B", b_shape, dtype)
+    R = _rnd(13, "R", (M, N), dtype, 4.0)
+    a64, b64 = A.astype(np.float64), B.astype(np.float64)
+    ref = a64 @ (b64.T if layout == tbp.NT else b64)
+    dA, dB, dR = to_dev(A, dtype), to_dev(B, dtype), to_dev(R, dtype)
+    ws = torch.empty(need + 4096, dtype=torch.uint8, device=DEV).fill_(0xA5)      # junk, larger than needed
+    got1 = tbp.tbp_gemm(layout, dA, dB, workspace=ws)
+    assert max_rel(to_np(got1), ref) < 4.5e-3
+    got2 = tbp.tbp_gemm(layout, dA, dB, workspace=ws)
+    assert torch.equal(got1, got2)
+    got3 = tbp.tbp_gemm(layout, dA, dB, R=dR, alpha=0.5, workspace=ws)
+    assert max_rel(to_np(got3), 0.5 * ref + R) < 4.5e-3
+    # without scratch the same call takes the ordinary path and agrees to rounding
+    plain = tbp.tbp_gemm(layout, dA, dB)
+    assert max_rel(to_np(plain), to_np(got1).astype(np.float64)) < 8e-3
+    # too small a workspace is not used (and not an error)
+    small = torch.empty(1024, dtype=torch.uint8, device=DEV)
+    assert max_rel(to_np(tbp.tbp_gemm(layout, dA, dB, workspace=small)), ref) < 4.5e-3
+
+
 def test_gemm_strided_views_and_empty():
     # operands that are column blocks of wider matrices (leading dimension > row length), as the stage uses them
     dtype = "bf16"
