@@ -404,9 +404,10 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   lds_f32* const strip = reinterpret_cast<lds_f32*>(lds + wave * (32 * SW * 4));
   static_assert(4 * 32 * SW * 4 <= NS * STAGE_BYTES, "strips must fit in the ring");
   constexpr int V = sizeof(OutT) == 4 ? 4 : 8;          // elements per 16-byte store
-  constexpr int LPR = WN / V, RPI = 64 / LPR;           // lanes per strip row, rows per wave-wide store
-  const int sr = lane / LPR, sc = (lane % LPR) * V;
-  const int gcol = n0 + wn * WN + sc;
+  // A strip is 32 rows of LPR 16-byte vectors; vector q (row q / LPR) is stored by lane q % 64 in pass q / 64, so
+  // a wave-wide store covers whole rows when LPR divides 64 and consecutive rows otherwise (WN = 96).
+  constexpr int LPR = WN / V, NVEC = 32 * LPR;
+  static_assert(NVEC % 64 == 0, "a strip must be a whole number of wave-wide stores");
 #pragma unroll
   for (int i = 0; i < TM; i++) {
 #pragma unroll
@@ -416,7 +417,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
         strip[(8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * SW + j * 32 + (lane & 31)] = p.alpha * acc[i][j][e];
     // what the strip needs from memory (old C for +=, residual or probabilities) is requested for the whole strip
     // first, so the stores below wait for one memory latency per strip instead of one per row group
-    constexpr int NIT = 32 / RPI, GRP = NIT < 8 ? NIT : 8;    // row groups per strip, and per request batch
+    constexpr int NIT = NVEC / 64, GRP = NIT < 8 ? NIT : 8;   // stores per strip, and per request batch
+    static_assert(NIT % GRP == 0, "request batches must tile the strip");
     const bool need_pre = (sizeof(OutT) == 4) ? false : (R != nullptr);   // (fp32 += reads its old value in place)
     __builtin_amdgcn_sched_barrier(0);      // keep the next strip's requests from being hoisted over this one
 #pragma unroll
@@ -425,7 +427,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
       float dl[GRP];
 #pragma unroll
       for (int u = 0; u < GRP; u++) {
-        const int grow = m0 + wm * WM + i * 32 + (g0 + u) * RPI + sr;
+        const int q = (g0 + u) * 64 + lane;
+        const int grow = m0 + wm * WM + i * 32 + q / LPR, gcol = n0 + wn * WN + (q % LPR) * V;
         if (need_pre && grow < p.M && gcol < p.N) {
           const long idx = (long)grow * p.ldc + gcol;
           pre[u] = *reinterpret_cast<const u32x4*>(R + idx);
@@ -434,8 +437,9 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
       }
 #pragma unroll
       for (int u = 0; u < GRP; u++) {
-        const int r = (g0 + u) * RPI + sr;
-        const int grow = m0 + wm * WM + i * 32 + r;
+        const int qv = (g0 + u) * 64 + lane;
+        const int r = qv / LPR, sc = (qv % LPR) * V;
+        const int grow = m0 + wm * WM + i * 32 + r, gcol = n0 + wn * WN + sc;
         if (grow < p.M && gcol < p.N) {     // N is a multiple of 8: a vector is inside or outside as a whole
           const long idx = (long)grow * p.ldc + gcol;
           float v[V];
@@ -700,17 +704,34 @@ static hipError_t launch_bf16(const GemmParams& p0, int batch, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Tiles 192 columns wide for the linear-layer products whose output fills the chip badly with 256 x 256 tiles (too
+// few of them, or a last round that is mostly empty): e.g. [2048, 5120] is 160 large tiles (62 % of a round) but 216
+// of the narrower ones (84 %).  Taken when the fraction of the rounds' capacity that is useful output, discounted
+// 7 % for the narrower tile's lower operand reuse, beats what the other choice gives by 8 %; the small-tile kernel,
+// which outputs of fewer than 192 large tiles otherwise use, counts as 0.60.
+static bool narrow_tiles_pay(int M, int N, int K) {
+  if (M < 256 || N < 192 || K <= 256) return false;
+  const long tiles_m = (M + 255) / 256;
+  const long t256 = tiles_m * ((N + 255) / 256), t192 = tiles_m * ((N + 191) / 192);
+  const double area = (double)M * N;
+  const double now = (N >= 256 && t256 >= 192) ? area / ((double)((t256 + 255) / 256) * 256 * 65536) : 0.60;
+  const double narrow = 0.93 * area / ((double)((t192 + 255) / 256) * 256 * 49152);
+  return t192 >= 192 && narrow > 1.08 * now;
+}
+
 // Cost model behind gemm_split_plan, fitted to measurements on this chip (microseconds): a round of large tiles costs
 // 0.0245 per contraction index plus 12 of prologue and epilogue; the exchange of partial sums costs about 30 plus
 // 0.67 per MiB of partials (they are written by every workgroup but read back by one workgroup per tile only); the
-// small-tile kernel that such outputs otherwise use sustains about 800 TFLOP/s.  In practice only long contractions
+// small-tile kernel that such outputs otherwise use sustains about 800 TFLOP/s when it has a tile for every compute
+// unit.  In practice only long contractions
 // pay: e.g. [2048, 5120] x K = 27648 runs in 590 us split three ways against 810 us.
 SplitPlan gemm_split_plan(int dtype, int layout, int M, int N, int K, int out_f32, int batch) {
   SplitPlan none{1, 0};
   if (dtype != 1 || out_f32 || batch != 1 || layout == TN || M < 256 || N < 256) return none;
   const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
-  if (tiles >= 192) return none;
-  double best = 2.0 * M * N * (double)K / 800e6;
+  if (tiles >= 192 || narrow_tiles_pay(M, N, K)) return none;
+  const long small_tiles = (long)((M + 127) / 128) * ((N + 127) / 128);      // (fewer than 256 of them leave CUs idle)
+  double best = 2.0 * M * N * (double)K / (800e6 * (small_tiles < 256 ? small_tiles / 256.0 : 1.0));
   int split = 1;
   for (int sp = 2; sp <= 8; sp++) {
     if (K / sp < 512) break;
@@ -825,6 +846,9 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
   // short contractions (the per-head q k^T and do v^T, K = head_dim) are all prologue and epilogue: small tiles let
   // two or three workgroups share a compute unit and overlap them
   const bool big = g.M >= 256 && g.N >= 256 && tiles_big >= 192 && g.K > 256;
+  if (!g.out_f32 && g.batch == 1 && g.causal == CAUSAL_NONE && !g.delta && g.layout != TN && narrow_tiles_pay(g.M, g.N, g.K))
+    return g.layout == NN ? launch_bf16<256, 192, true, false, bf16_t, 64>(p, 1, s)
+                          : launch_bf16<256, 192, true, true, bf16_t, 64>(p, 1, s);
   if (g.ws && g.causal == CAUSAL_NONE && !g.delta && reinterpret_cast<uintptr_t>(g.ws) % 256 == 0) {
     const SplitPlan plan = gemm_split_plan(dtype, g.layout, g.M, g.N, g.K, g.out_f32, g.batch);
     if (plan.split > 1 && plan.bytes <= g.ws_bytes)

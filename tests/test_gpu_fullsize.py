@@ -56,13 +56,11 @@ def test_mlp_config_real_shape_full_compare():
 
 
 @pytest.mark.timeout(600)
-def test_13b_mlp_block_shape_with_split_contraction():
-    """The MLP half of a 13B-shaped layer (d_model 5120, FFN 13824, 2048 tokens per micro-batch): its backward-p1
-    product dh2 = [dg, du] Wgu^T has a [2048, 5120] output (160 large tiles) and a contraction of 27648, the case
-    the stage runs with the contraction split over several workgroups per tile.  Every tensor is compared, twice in
-    a row on the same stage (the arrival counters in the stage's scratch are reused without being cleared again)."""
+def test_13b_mlp_block_shape_full_compare():
+    """The MLP half of a 13B-shaped layer (d_model 5120, FFN 13824, 2048 tokens per micro-batch): [2048, 5120] outputs
+    are 160 tiles of 256 x 256, which the forward and backward-p1 products run on 256 x 192 tiles instead.  Every
+    tensor is compared, twice in a row on the same stage."""
     shape = si.StageShape("mlp_13b_block", 1, 5120, 0, 0, 13824, 2048, 1, 2, "bf16", 20240524)
-    assert tbp.lib().tbp_gemm_workspace_bytes(tbp.TBP_BF16, tbp.NT, shape.tokens, shape.d_model, 2 * shape.d_ffn, 0) > 0
     print(f"13B MLP block {shape}", flush=True)
     params, xs, dys = _inputs(shape)
     outs, dxs, grads = run_oracle(shape, params, xs, dys)
@@ -74,6 +72,26 @@ def test_13b_mlp_block_shape_with_split_contraction():
         st.backward_p2([0, 1], tbp.TBP_P2_KCONCAT, accumulate=False)
         torch.cuda.synchronize()
         compare_stage(shape, g_outs, g_dxs, st.grads, outs, dxs, grads, stage_tolerance("bf16"), f"13B MLP block, pass {rep}")
+    st.close()
+
+
+@pytest.mark.timeout(600)
+def test_stage_with_split_contraction():
+    """A stage whose backward-p1 product dh2 = [dg, du] Wgu^T has a small output ([1024, 1024]: 16 large tiles) and a
+    very long contraction (2 x 24576): the stage runs it with the contraction split over several workgroups per tile,
+    using scratch from its own workspace, whose arrival counters are cleared once and then reused."""
+    shape = si.StageShape("mlp_long_k", 1, 1024, 0, 0, 24576, 1024, 1, 2, "bf16", 20240525)
+    assert tbp.lib().tbp_gemm_workspace_bytes(tbp.TBP_BF16, tbp.NT, shape.tokens, shape.d_model, 2 * shape.d_ffn, 0) > 0
+    params, xs, dys = _inputs(shape)
+    outs, dxs, grads = run_oracle(shape, params, xs, dys)
+    print("oracle done", flush=True)
+    st = make_gpu_stage(shape, params)
+    for rep in range(2):
+        g_outs = [st.forward(m, to_dev(xs[m], "bf16")) for m in range(2)]
+        g_dxs = [st.backward_p1(m, to_dev(dys[m], "bf16")) for m in range(2)]
+        st.backward_p2([0, 1], tbp.TBP_P2_KCONCAT, accumulate=False)
+        torch.cuda.synchronize()
+        compare_stage(shape, g_outs, g_dxs, st.grads, outs, dxs, grads, stage_tolerance("bf16"), f"long-K MLP, pass {rep}")
     st.close()
 
 

@@ -30,6 +30,8 @@ GEMM_SHAPES = [  # (M, N, K): several tiles plus ragged tails in every dimension
     (4096, 4344, 72), (4344, 4096, 40),     # 272 large tiles: the output is cut into whole rounds + a small-tile rest
     # long contractions on 192 / 272 large tiles with a ragged last tile in M, N and K (the weight-gradient kernel)
     (4096, 3064, 264), (3064, 4096, 1000), (4096, 4344, 328),
+    # outputs that fill the chip badly with 256 x 256 tiles: the storage-type NN / NT products take 256 x 192 tiles
+    (2040, 5128, 328), (1024, 11016, 200),
 ]
 
 
@@ -60,7 +62,7 @@ def test_gemm_matches_definition(dtype, layout, mnk):
 
 
 @pytest.mark.parametrize("layout", [tbp.NN, tbp.NT])
-@pytest.mark.parametrize("mnk", [(1024, 4096, 32768), (1000, 4040, 32776), (2048, 5120, 27648)])
+@pytest.mark.parametrize("mnk", [(1024, 4096, 32768), (1000, 4040, 32776), (1280, 2304, 49152)])
 def test_gemm_with_split_contraction(layout, mnk):
     """bf16 products whose output is too small to fill the chip: given scratch memory, several workgroups share a tile
     and their partial sums meet in the scratch.  Same result as the definition, identical from call to call (the
