@@ -417,7 +417,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
         strip[(8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * SW + j * 32 + (lane & 31)] = p.alpha * acc[i][j][e];
     // what the strip needs from memory (old C for +=, residual or probabilities) is requested for the whole strip
     // first, so the stores below wait for one memory latency per strip instead of one per row group
-    constexpr int NIT = NVEC / 64, GRP = NIT < 8 ? NIT : 8;   // stores per strip, and per request batch
+    constexpr int NIT = NVEC / 64;                            // stores per strip, and per request batch:
+    constexpr int GRP = NIT <= 8 ? NIT : (NIT % 8 == 0 ? 8 : (NIT % 6 == 0 ? 6 : 4));
     static_assert(NIT % GRP == 0, "request batches must tile the strip");
     const bool need_pre = (sizeof(OutT) == 4) ? false : (R != nullptr);   // (fp32 += reads its old value in place)
     __builtin_amdgcn_sched_barrier(0);      // keep the next strip's requests from being hoisted over this one
@@ -863,10 +864,20 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
                    : dispatch_layout<128, 128, bf16_t>(g.layout, q, g.batch, s);
   };
   // Tail quantisation: with nt large tiles on 256 compute units the last round runs nt % 256 workgroups.  When
-  // that round would be less than half full, the output is cut along its longer side into a part made of whole
-  // rounds of large tiles and a remainder that is run with 128 x 128 tiles (four times as many workgroups).
+  // that round would be at most three quarters full, the output is cut along its longer side into a part made of
+  // whole rounds of large tiles and a remainder: up to half a round's worth runs on 128 x 128 tiles (four times as
+  // many workgroups), more than that on 256 x 192 tiles where that kernel exists for the layout (4/3 as many
+  // workgroups: one nearly full round of tiles that take 3/4 of the time).
   const long rem = tiles_big % 256;
-  if (big && g.batch == 1 && g.causal == CAUSAL_NONE && tiles_big > 256 && rem != 0 && rem <= 128) {
+  const bool has_narrow = (g.out_f32 && g.layout == TN) || (!g.out_f32 && g.layout != TN && !g.delta);
+  auto run_rest = [&](const GemmParams& q) -> hipError_t {
+    const long t192 = (long)((q.M + 255) / 256) * ((q.N + 191) / 192);
+    if (rem <= 128 || !has_narrow || t192 > 256) return run(q, rem > 128);
+    if (g.out_f32) return launch_bf16<256, 192, false, false, float, 32>(q, 1, s);
+    return g.layout == NN ? launch_bf16<256, 192, true, false, bf16_t, 64>(q, 1, s)
+                          : launch_bf16<256, 192, true, true, bf16_t, 64>(q, 1, s);
+  };
+  if (big && g.batch == 1 && g.causal == CAUSAL_NONE && tiles_big > 256 && rem != 0 && (rem <= 128 || (has_narrow && rem <= 192))) {
     const long whole = tiles_big - rem;
     const size_t ce = g.out_f32 ? 4 : 2;
     GemmParams a = p, b = p;
@@ -880,7 +891,7 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
         b.C = (char*)p.C + n0 * ce;
         if (p.R) b.R = (const char*)p.R + n0 * 2;
         hipError_t e = run(a, true);
-        return e != hipSuccess ? e : run(b, false);
+        return e != hipSuccess ? e : run_rest(b);
       }
     } else {                                        // cut along M
       const int rows = (int)(whole / tiles_n);
@@ -892,7 +903,7 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
         b.C = (char*)p.C + m0 * g.ldc * ce;
         if (p.R) b.R = (const char*)p.R + m0 * g.ldc * 2;
         hipError_t e = run(a, true);
-        return e != hipSuccess ? e : run(b, false);
+        return e != hipSuccess ? e : run_rest(b);
       }
     }
   }

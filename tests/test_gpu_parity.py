@@ -32,6 +32,8 @@ GEMM_SHAPES = [  # (M, N, K): several tiles plus ragged tails in every dimension
     (4096, 3064, 264), (3064, 4096, 1000), (4096, 4344, 328),
     # outputs that fill the chip badly with 256 x 256 tiles: the storage-type NN / NT products take 256 x 192 tiles
     (2040, 5128, 328), (1024, 11016, 200),
+    # 432 large tiles: one whole round + 176, the rest of which runs on 256 x 192 tiles (cut along N, and along M)
+    (4096, 6904, 264), (6904, 4096, 136),
 ]
 
 
