@@ -150,3 +150,26 @@ def test_single_op_argument_checks():
     assert L.tbp_softmax_fwd(1, 1, 8192, 1, fake, fake, None) == 1
     assert L.tbp_rope(1, 4, 8, 2, 24, 48, fake, 0, fake, None) == 1
     assert L.tbp_rmsnorm_p1_scratch_bytes(4096) == 256 * 4096 * 4
+
+
+def test_gemm_workspace_policy_and_checks():
+    """tbp_gemm_workspace_bytes is host arithmetic: scratch is asked for only where splitting the contraction pays
+    (a bf16 NN / NT product with a storage-type output that neither tile shape can spread over the chip, and a long
+    contraction), and it is exactly the arrival counters plus one fp32 tile per slice."""
+    L = tbp.lib()
+    need = L.tbp_gemm_workspace_bytes(1, tbp.NT, 1024, 4096, 32768, 0)
+    assert need == 1024 + 64 * 4 * 256 * 256 * 4                          # 64 tiles, four slices
+    assert L.tbp_gemm_workspace_bytes(1, tbp.NN, 1024, 4096, 32768, 0) == need
+    for args in [(1, tbp.TN, 1024, 4096, 32768, 0),      # weight-gradient layout: never split
+                 (1, tbp.NT, 1024, 4096, 32768, 1),      # fp32 output
+                 (0, tbp.NT, 1024, 4096, 32768, 0),      # fp32 storage
+                 (1, tbp.NT, 4096, 4096, 32768, 0),      # 256 large tiles already fill the chip
+                 (1, tbp.NT, 2048, 5120, 27648, 0),      # 216 tiles of 256 x 192 do
+                 (1, tbp.NT, 1024, 4096, 4096, 0),       # short contraction: the exchange would cost more than it saves
+                 (1, tbp.NT, 0, 4096, 32768, 0), (1, 7, 1024, 4096, 32768, 0)]:
+        assert L.tbp_gemm_workspace_bytes(*args) == 0, args
+    fake = C.c_void_p(0x2000000)
+    # a misaligned workspace is refused before anything is launched
+    assert L.tbp_gemm_ws(1, tbp.NT, 1024, 4096, 32768, 1.0, fake, 32768, fake, 32768, fake, 4096, 0, 0, None,
+                         C.c_void_p(0x3000010), need, None) == 1
+    assert "aligned" in L.tbp_last_error().decode()
