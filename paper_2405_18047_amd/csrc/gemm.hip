@@ -1,9 +1,11 @@
 // GEMM kernels for gfx950 (MI355X).
 //
 // bf16 path: C = alpha * op(A) op(B) on the 32x32x16 bf16 MFMA instruction, fp32 accumulation.
-//   One workgroup = 4 wavefronts (2 x 2), block tile BM x BN, contraction consumed in slices of 32 through a
-//   4-slot LDS ring that is filled by asynchronous global -> LDS copies (no staging registers), so three
-//   slices are in flight while one is multiplied.
+//   One workgroup = 4 wavefronts (2 x 2), block tile BM x BN (256 x 256, 256 x 192 or 128 x 128, chosen per product by
+//   how well the tiles fill the 256 compute units), contraction consumed in slices of 32 through a 4-slot LDS ring, or
+//   in slices of 64 through two slots where the contraction index is contiguous in memory, filled by asynchronous
+//   global -> LDS copies (no staging registers) that stay in flight while the previous slices are multiplied.
+//   Outputs too small for any of that can split the contraction over several workgroups per tile (scratch memory).
 //   An operand whose contraction index is contiguous in memory ("KC": A of NN/NT, B of NT) is kept in
 //   LDS as [row][k] and read as 16-byte vectors; an operand whose contraction index is the slow,
 //   strided one ("KS": A of TN, B of NN/TN, i.e. both operands of dW = X^T dY) is kept as [k][row]
