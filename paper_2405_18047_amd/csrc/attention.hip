@@ -249,8 +249,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 
 // ------------------------------------------------------------------------------------------ backward-p1: dK, dV, dS^T
-// One workgroup = 4 waves x 32 keys of one (sequence, head); queries, their output derivatives and their row
-// statistics stream through LDS in steps of 64 queries, double-buffered.  Per 32 queries and wave:
+// One workgroup = 128 keys of one (sequence, head), 32 per wave pair; queries, their output derivatives and their row
+// statistics stream through LDS in steps of 64 queries, three steps deep.  Per 32 queries and wave pair:
 //   S = Q K^T and dP = dO V^T (column = key; K and V rows of the lane's key stay in registers as B operands),
 //   P = exp2(S c - lse), dS = P (dP - delta), then dV^T += dO^T P and dK^T += Q^T dS with P and dS fed from the
 //   accumulators (see the file header).  dS^T is also written out ([key][query], storage type): dQ = dS K is a
@@ -266,40 +266,124 @@ struct AttnBwdParams {
   float scale, scale_log2e;
 };
 
+// The two kinds of work run on different waves.  A single wave issues in order: while it works through the ~200 vector
+// instructions that turn S and dP into P and dS, the matrix pipe of its SIMD idles, and the other way round (a
+// single-wave form of this kernel, software-pipelined three tiles deep, kept the matrix pipe 27 % busy and was 5 %
+// slower).  A workgroup is 8 waves, two per SIMD, of which
+//   waves 0..3 ("left")   compute S = Q K^T and dP = dO V^T for their 32 keys, then P and dS, write dS^T out and hand
+//                         P and dS (already in B-operand form, 64 bytes per lane) over through LDS;
+//   waves 4..7 ("right")  take P and dS of the previous tile from LDS and accumulate dV^T += dO^T P, dK^T += Q^T dS.
+// The hardware interleaves the two instruction streams of a SIMD, so the vector work of one tile runs under the MFMAs
+// of its neighbours.  One workgroup barrier per 32-query tile; the hand-over buffers and the query-step images are
+// double / triple buffered so that neither side ever waits for the other beyond that barrier.  The right waves also
+// issue all asynchronous copies (they have no other vector-memory operations, so their copy counter is exact).
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_kv_kernel(AttnBwdParams p) {
+__global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p) {
   using HT = HeadTile<DH>;
   constexpr int KS = DH / 16, DT = DH / 32, BQ = 64;
   constexpr int IMG = BQ * HT::RB, SLOT = 2 * IMG + 1024;     // Q image, dO image, 64 x (lse, delta); three slots
-  constexpr int NCH = IMG / 1024 / 4;
+  constexpr int NCH = IMG / 1024 / 4;                         // copies per right wave and image
+  constexpr int OPS = 2 * NCH + 1;                            // vector-memory operations of one issue(), per right wave
+  constexpr int HAND = 4 * 4096;                              // one hand-over buffer: 4 wave pairs x 64 lanes x 64 bytes
+  constexpr int HALF = 32 * HT::RB;                           // the second tile's rows inside an image
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   lds_u8* const lds = LDS_PTR(unsigned char, smem_raw);
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+  lds_u8* const hand = lds + 3 * SLOT;
 
   const int tid = threadIdx.x, lane = tid & 63, kl = lane & 31, g = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int kb = blockIdx.y;                                  // key blocks in order: with causal masking the first are the longest
+  const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int right = wave8 >> 2, wave = wave8 & 3;             // role, and which 32 keys of the block
+  const int kb = blockIdx.y;
   const int h = (int)blockIdx.x % p.H, b = (int)blockIdx.x / p.H;
   const int kv0 = kb * 128, kw0 = kv0 + 32 * wave, key = kw0 + kl;
   const int d = p.H * DH;
   const long tok0 = (long)b * p.S;
   const long bh = (long)b * p.H + h;
-
-  // ---- the lane's key row and value row as B operands (8 consecutive head-dim values per k-step)
-  bf16x8 kfb[KS], vfb[KS];
-  {
-    const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.qkv + tok0 * p.ld_qkv + d + h * DH, (uint32_t)((long)p.S * p.ld_qkv * 2));
-    const unsigned off = key < p.S ? (unsigned)(((long)key * p.ld_qkv + 8 * g) * 2) : kOob;
-#pragma unroll
-    for (int s = 0; s < KS; s++) {
-      kfb[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, 32 * s, 0));
-      vfb[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, 32 * s + 2 * d, 0));
-    }
-  }
-  wait_vmem<0>();       // see the forward kernel: no compiler-inserted wait for these may remain inside the loop
-
   const typename HT::Offsets fo = HT::offsets(lane);
+  const int step0 = p.causal ? kv0 / BQ : 0;                  // queries before the first key of the block see none of it
+  const int nstep = (p.S + BQ - 1) / BQ;
+  const int t0 = 2 * step0, nt = 2 * (nstep - step0);         // first tile, number of tiles
+  typedef LDS_AS float lds_f32;
+  lds_u8* const my_hand = hand + wave * 4096 + lane * 16;     // + buffer * HAND + 1024 * {p0, p1, s0, s1}
+
+  if (!right) {
+    // ------------------------------------------------------------------ left: S, dP, P, dS, dS^T out
+    bf16x8 kfb[KS], vfb[KS];
+    {
+      const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.qkv + tok0 * p.ld_qkv + d + h * DH, (uint32_t)((long)p.S * p.ld_qkv * 2));
+      const unsigned off = key < p.S ? (unsigned)(((long)key * p.ld_qkv + 8 * g) * 2) : kOob;
+#pragma unroll
+      for (int s = 0; s < KS; s++) {
+        kfb[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, 32 * s, 0));
+        vfb[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, 32 * s + 2 * d, 0));
+      }
+    }
+    const u32x4 rst = make_desc(p.dst + bh * p.S * p.S, (uint32_t)((long)p.S * p.S * 2));
+    const unsigned st_off = key < p.S ? (unsigned)(((long)key * p.S + 4 * g) * 2) : kOob;
+    __syncthreads();                                          // steps step0 and step0 + 1 have landed (right waves waited)
+    for (int it = 0; it <= nt; it++) {
+      if (it < nt) {
+        const int tile = t0 + it, qt0 = tile * 32;
+        lds_u8* const slot = lds + ((tile >> 1) % 3) * SLOT;
+        lds_u8* const qimg = slot + (tile & 1) * HALF;
+        lds_u8* const dimg = qimg + IMG;
+        const lds_f32* const stat = reinterpret_cast<const lds_f32*>(slot + 2 * IMG) + 32 * (tile & 1);
+        f32x16 sa, da;
+#pragma unroll
+        for (int e = 0; e < 16; e++) { sa[e] = 0.f; da[e] = 0.f; }
+        constexpr int PF = KS < 4 ? KS : 4;
+        bf16x8 fq[KS], fd[KS];
+#pragma unroll
+        for (int s = 0; s < PF; s++) { fq[s] = HT::rows_frag(qimg, fo, 0, s); fd[s] = HT::rows_frag(dimg, fo, 0, s); }
+#pragma unroll
+        for (int s = 0; s < KS; s++) {
+          if (s + PF < KS) { fq[s + PF] = HT::rows_frag(qimg, fo, 0, s + PF); fd[s + PF] = HT::rows_frag(dimg, fo, 0, s + PF); }
+          sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[s], kfb[s], sa, 0, 0, 0);
+          da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[s], vfb[s], da, 0, 0, 0);
+        }
+        // register e of the tile is query qt0 + 8 (e / 4) + 4 g + e % 4
+        const int rel = p.causal ? key - qt0 - 4 * g : -1;
+        float pv[16], sv[16];
+#pragma unroll
+        for (int e4 = 0; e4 < 4; e4++) {
+          const f32x4 ls = *reinterpret_cast<const LDS_AS f32x4*>(stat + 8 * e4 + 4 * g);
+          const f32x4 dl = *reinterpret_cast<const LDS_AS f32x4*>(stat + BQ + 8 * e4 + 4 * g);
+#pragma unroll
+          for (int q = 0; q < 4; q++) {
+            const int e = 4 * e4 + q;
+            float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(sa[e], p.scale_log2e, -ls[q]));
+            pe = (8 * e4 + q < rel) ? 0.f : pe;
+            pv[e] = pe;
+            sv[e] = pe * (da[e] - dl[q]);
+          }
+        }
+        bf16x8 kp[2], ks[2];
+#pragma unroll
+        for (int u = 0; u < 2; u++)
+#pragma unroll
+          for (int t = 0; t < 8; t++) { kp[u][t] = (bf16_t)pv[8 * u + t]; ks[u][t] = (bf16_t)sv[8 * u + t]; }
+        lds_u8* const out = my_hand + (tile & 1) * HAND;
+        *reinterpret_cast<LDS_AS bf16x8*>(out) = kp[0];
+        *reinterpret_cast<LDS_AS bf16x8*>(out + 1024) = kp[1];
+        *reinterpret_cast<LDS_AS bf16x8*>(out + 2048) = ks[0];
+        *reinterpret_cast<LDS_AS bf16x8*>(out + 3072) = ks[1];
+        // dS^T out: the two halves of each packed k-step are four consecutive queries of the lane's key row.  Nobody
+        // reads it before the kernel ends, so the stores go out untracked: the barrier below must not wait for them
+        // (tracked, their acknowledgements cost a quarter of the kernel's time).
+        const u32x4 s0 = __builtin_bit_cast(u32x4, ks[0]), s1 = __builtin_bit_cast(u32x4, ks[1]);
+        const u32x2 dsv[4] = {u32x2{s0[0], s0[1]}, u32x2{s0[2], s0[3]}, u32x2{s1[0], s1[1]}, u32x2{s1[2], s1[3]}};
+#pragma unroll
+        for (int e4 = 0; e4 < 4; e4++)
+          store8_async(dsv[e4], rst, qt0 + 8 * e4 < p.S ? st_off : kOob, (uint32_t)__builtin_amdgcn_readfirstlane((qt0 + 8 * e4) * 2));
+      }
+      __syncthreads();
+    }
+    return;
+  }
+
+  // -------------------------------------------------------------------- right: copies, dV^T, dK^T
   int c_row[NCH];
   unsigned cq_off[NCH], cd_off[NCH];
 #pragma unroll
@@ -307,149 +391,73 @@ __global__ __launch_bounds__(256) void attn_bwd_kv_kernel(AttnBwdParams p) {
     HT::plan(wave + 4 * i, lane, p.ld_qkv, c_row[i], cq_off[i]);
     HT::plan(wave + 4 * i, lane, p.ld_do, c_row[i], cd_off[i]);
   }
-  const int step0 = p.causal ? kv0 / BQ : 0;                  // queries before the first key of the block see none of it
-  const int nstep = (p.S + BQ - 1) / BQ;
-  typedef LDS_AS float lds_f32;
-  auto issue = [&](int i, int slot_off) {          // step i into the slot at byte offset slot_off
+  // Every call issues exactly OPS operations per wave (steps past the end write zeros into their slot and fetch
+  // nothing), so a wait for "all but the last issue" is a fixed count.
+  auto issue = [&](int i) {
     const int q0 = i * BQ;
-    const uint32_t slot = lds0 + slot_off;
-    const u32x4 dq = make_desc(p.qkv + (tok0 + q0) * p.ld_qkv + h * DH, (uint32_t)((long)(p.S - q0) * p.ld_qkv * 2));
-    const u32x4 dd = make_desc(p.dout + (tok0 + q0) * p.ld_do + h * DH, (uint32_t)((long)(p.S - q0) * p.ld_do * 2));
+    const bool live = i < nstep;
+    const uint32_t slot = lds0 + (i % 3) * SLOT;
+    const int qs = live ? q0 : 0;
+    const u32x4 dq = make_desc(p.qkv + (tok0 + qs) * p.ld_qkv + h * DH, (uint32_t)((long)(p.S - qs) * p.ld_qkv * 2));
+    const u32x4 dd = make_desc(p.dout + (tok0 + qs) * p.ld_do + h * DH, (uint32_t)((long)(p.S - qs) * p.ld_do * 2));
 #pragma unroll
     for (int c = 0; c < NCH; c++) {
-      const bool ok = q0 + c_row[c] < p.S;
+      const bool ok = live && q0 + c_row[c] < p.S;
       dma16(slot + wave * 1024 + c * 4096, dq, ok ? cq_off[c] : kOob);
       dma16(slot + IMG + wave * 1024 + c * 4096, dd, ok ? cd_off[c] : kOob);
     }
-    // row statistics of the step, by the same asynchronous path (a register load here would make the compiler wait
-    // for every copy just issued): wave 0 fetches lse[0..63], wave 1 delta[0..63], one dword per lane
-    if (wave < 2) {
-      const int q = q0 + lane;
-      const u32x4 ds = wave == 0 ? make_desc(p.lse + bh * p.S, (uint32_t)(p.S * 4))
-                                 : make_desc(p.delta + tok0 * p.H + h, (uint32_t)(((long)(p.S - 1) * p.H + 1) * 4));
-      const unsigned off = q < p.S ? (unsigned)(wave == 0 ? q * 4 : (long)q * p.H * 4) : kOob;
-      dma4(slot + 2 * IMG + wave * 256, ds, off);
-    }
+    // row statistics: wave 0 fetches lse[0..63], wave 1 delta[0..63]; waves 2 and 3 issue the same instruction out of
+    // range (nothing moves) to keep the count uniform.  Their 256 bytes land behind the two statistics rows.
+    const int q = q0 + lane;
+    const u32x4 ds = (wave & 1) == 0 ? make_desc(p.lse + bh * p.S, (uint32_t)(p.S * 4))
+                                     : make_desc(p.delta + tok0 * p.H + h, (uint32_t)(((long)(p.S - 1) * p.H + 1) * 4));
+    const unsigned off = (live && wave < 2 && q < p.S) ? (unsigned)((wave & 1) == 0 ? q * 4 : (long)q * p.H * 4) : kOob;
+    dma4(slot + 2 * IMG + wave * 256, ds, off);
   };
-
   f32x16 dvt[DT], dkt[DT];
 #pragma unroll
   for (int t = 0; t < DT; t++)
 #pragma unroll
     for (int e = 0; e < 16; e++) { dvt[t][e] = 0.f; dkt[t][e] = 0.f; }
 
-  // dS^T of this (sequence, head) through a buffer resource: the lane's key row and half are the vector offset, the
-  // query of a register group the scalar one; keys past the end are redirected out of range (dropped)
-  const __amdgpu_buffer_rsrc_t rst = make_rsrc(p.dst + bh * p.S * p.S, (uint32_t)((long)p.S * p.S * 2));
-  const unsigned st_off = key < p.S ? (unsigned)(((long)key * p.S + 4 * g) * 2) : kOob;
-  // Three phases per 32-query tile: (1) S and dP on the matrix pipe, (2) P, dS, their bf16 forms and the dS^T store on
-  // the vector pipe, (3) dV^T and dK^T on the matrix pipe.  A wave runs them as a software pipeline three tiles deep -
-  // at time k: phase 1 of tile k, phase 2 of tile k-1, phase 3 of tile k-2, all independent of each other - so the vector
-  // work of one tile sits between the MFMAs of its neighbours instead of stalling the matrix pipe (one wave per SIMD:
-  // nothing else would fill it).  Two tiles per step of 64 queries, three slots: steps i (read by phases 2 and 3) and
-  // i+1 (read by phase 1) are live while step i+2 lands.
-  struct Raw { f32x16 s, d; };
-  struct Packed { bf16x8 p[2], s[2]; };
-  auto phase1 = [&](lds_u8* qimg, Raw& r) {                       // qimg: the tile's 32 rows of the step's Q image
-    lds_u8* const dimg = qimg + IMG;
+  issue(step0);
+  issue(step0 + 1);
+  wait_vmem<0>();
+  __syncthreads();
+  for (int it = 0; it <= nt; it++) {
+    const int tp = t0 + it;                                   // the tile the left waves are on
+    if (it > 0) {
+      const int tile = tp - 1;
+      lds_u8* const qimg = lds + ((tile >> 1) % 3) * SLOT + (tile & 1) * HALF;
+      lds_u8* const dimg = qimg + IMG;
+      const lds_u8* const in = my_hand + (tile & 1) * HAND;
+      bf16x8 kp[2], ks[2];
+      kp[0] = *reinterpret_cast<const LDS_AS bf16x8*>(in);
+      kp[1] = *reinterpret_cast<const LDS_AS bf16x8*>(in + 1024);
+      ks[0] = *reinterpret_cast<const LDS_AS bf16x8*>(in + 2048);
+      ks[1] = *reinterpret_cast<const LDS_AS bf16x8*>(in + 3072);
+      constexpr int N = 2 * DT, PF = N < 3 ? N : 3;           // (u, t) pairs; fragments requested PF pairs ahead
+      bf16x8 fo_d[N], fo_q[N];
 #pragma unroll
-    for (int e = 0; e < 16; e++) { r.s[e] = 0.f; r.d[e] = 0.f; }
-    // fragments requested PF k-steps ahead of their MFMA: an LDS read takes several MFMA issue slots to return
-    constexpr int PF = KS < 4 ? KS : 4;
-    bf16x8 fq[KS], fd[KS];
+      for (int j = 0; j < PF; j++) { fo_d[j] = HT::cols_frag(dimg, fo, 0, j / DT, j % DT); fo_q[j] = HT::cols_frag(qimg, fo, 0, j / DT, j % DT); }
 #pragma unroll
-    for (int s = 0; s < PF; s++) { fq[s] = HT::rows_frag(qimg, fo, 0, s); fd[s] = HT::rows_frag(dimg, fo, 0, s); }
-#pragma unroll
-    for (int s = 0; s < KS; s++) {
-      if (s + PF < KS) { fq[s + PF] = HT::rows_frag(qimg, fo, 0, s + PF); fd[s + PF] = HT::rows_frag(dimg, fo, 0, s + PF); }
-      r.s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[s], kfb[s], r.s, 0, 0, 0);
-      r.d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[s], vfb[s], r.d, 0, 0, 0);
-    }
-  };
-  // register e of a tile is query qt0 + 8 (e / 4) + 4 g + e % 4; statistics fetched four rows at a time
-  auto phase2 = [&](const lds_f32* stat, int qt0, const Raw& r, Packed& k) {   // arithmetic only; phase2_store writes dS^T
-    const int rel = p.causal ? key - qt0 - 4 * g : -1;            // register rows (relative to 4 g) below it: query before the key
-    float pv[16], sv[16];
-#pragma unroll
-    for (int e4 = 0; e4 < 4; e4++) {
-      const f32x4 ls = *reinterpret_cast<const LDS_AS f32x4*>(stat + 8 * e4 + 4 * g);
-      const f32x4 dl = *reinterpret_cast<const LDS_AS f32x4*>(stat + BQ + 8 * e4 + 4 * g);
-#pragma unroll
-      for (int q = 0; q < 4; q++) {
-        const int e = 4 * e4 + q;
-        float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(r.s[e], p.scale_log2e, -ls[q]));
-        pe = (8 * e4 + q < rel) ? 0.f : pe;
-        pv[e] = pe;
-        sv[e] = pe * (r.d[e] - dl[q]);
+      for (int j = 0; j < N; j++) {
+        if (j + PF < N) {
+          fo_d[j + PF] = HT::cols_frag(dimg, fo, 0, (j + PF) / DT, (j + PF) % DT);
+          fo_q[j + PF] = HT::cols_frag(qimg, fo, 0, (j + PF) / DT, (j + PF) % DT);
+        }
+        dvt[j % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo_d[j], kp[j / DT], dvt[j % DT], 0, 0, 0);
+        dkt[j % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo_q[j], ks[j / DT], dkt[j % DT], 0, 0, 0);
       }
     }
-#pragma unroll
-    for (int u = 0; u < 2; u++)
-#pragma unroll
-      for (int t = 0; t < 8; t++) { k.p[u][t] = (bf16_t)pv[8 * u + t]; k.s[u][t] = (bf16_t)sv[8 * u + t]; }
-  };
-  // dS^T out: the two halves of each packed k-step are four consecutive queries of the lane's key row
-  auto phase2_store = [&](int qt0, const Packed& k) {
-    const u32x4 s0 = __builtin_bit_cast(u32x4, k.s[0]), s1 = __builtin_bit_cast(u32x4, k.s[1]);
-    const u32x2 dsv[4] = {u32x2{s0[0], s0[1]}, u32x2{s0[2], s0[3]}, u32x2{s1[0], s1[1]}, u32x2{s1[2], s1[3]}};
-    if (qt0 + 32 <= p.S) {
-#pragma unroll
-      for (int e4 = 0; e4 < 4; e4++) __builtin_amdgcn_raw_buffer_store_b64(dsv[e4], rst, st_off, (qt0 + 8 * e4) * 2, 0);
-    } else {                                                      // ragged last tile (seq is a multiple of 8), or past the end
-#pragma unroll
-      for (int e4 = 0; e4 < 4; e4++)
-        if (qt0 + 8 * e4 < p.S) __builtin_amdgcn_raw_buffer_store_b64(dsv[e4], rst, st_off, (qt0 + 8 * e4) * 2, 0);
-    }
-  };
-  auto phase3 = [&](lds_u8* qimg, const Packed& k) {              // dV^T += dO^T P, dK^T += Q^T dS
-    lds_u8* const dimg = qimg + IMG;
-    constexpr int N = 2 * DT, PF = N < 3 ? N : 3;                 // (u, t) pairs; fragments requested PF pairs ahead
-    bf16x8 fo_d[N], fo_q[N];
-#pragma unroll
-    for (int j = 0; j < PF; j++) { fo_d[j] = HT::cols_frag(dimg, fo, 0, j / DT, j % DT); fo_q[j] = HT::cols_frag(qimg, fo, 0, j / DT, j % DT); }
-#pragma unroll
-    for (int j = 0; j < N; j++) {
-      if (j + PF < N) {
-        fo_d[j + PF] = HT::cols_frag(dimg, fo, 0, (j + PF) / DT, (j + PF) % DT);
-        fo_q[j + PF] = HT::cols_frag(qimg, fo, 0, (j + PF) / DT, (j + PF) % DT);
-      }
-      dvt[j % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo_d[j], k.p[j / DT], dvt[j % DT], 0, 0, 0);
-      dkt[j % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo_q[j], k.s[j / DT], dkt[j % DT], 0, 0, 0);
-    }
-  };
-  auto stat_of = [&](int slot_off, int qt) { return reinterpret_cast<const lds_f32*>(lds + slot_off + 2 * IMG) + 32 * qt; };
-  constexpr int HALF = 32 * HT::RB;                               // the second tile's rows inside an image
-
-  if (step0 < nstep) {
-    int s_cur = 0, s_nxt = SLOT, s_far = 2 * SLOT;                // slots of step i, i+1, i+2
-    issue(step0, s_cur);
-    wait_vmem<0>();
+    // step (tp + 1) / 2 + 1 is what the left waves start two barriers from now, when tp is odd: it was issued three
+    // barriers ago and only the issue after it may still be in flight
+    if (tp & 1) wait_vmem<OPS>();
     __syncthreads();
-    if (step0 + 1 < nstep) issue(step0 + 1, s_nxt);
-    Raw r0, r1;
-    Packed k0, k1;
-    phase1(lds + s_cur, r0);                                      // time 2 step0
-    phase1(lds + s_cur + HALF, r1);                               // time 2 step0 + 1
-    phase2(stat_of(s_cur, 0), 2 * step0 * 32, r0, k0);
-    phase2_store(2 * step0 * 32, k0);
-    for (int i = step0; i < nstep; i++) {
-      // tiles 2i (packed in k0) and 2i+1 (raw in r1) are in flight; step i+1 must have landed for the next phase 1
-      if (i + 1 < nstep) {
-        wait_vmem<0>();
-        __syncthreads();                                          // also: every wave is done with step i-1 (slot s_far)
-        if (i + 2 < nstep) issue(i + 2, s_far);
-      }
-      phase1(lds + s_nxt, r0);                                    // tile 2i+2 (stale slot contents past the end: unused)
-      phase2(stat_of(s_cur, 1), (2 * i + 1) * 32, r1, k1);        // tile 2i+1
-      phase2_store((2 * i + 1) * 32, k1);
-      phase3(lds + s_cur, k0);                                    // tile 2i
-      phase1(lds + s_nxt + HALF, r1);                             // tile 2i+3
-      phase2(stat_of(s_nxt, 0), (2 * i + 2) * 32, r0, k0);        // tile 2i+2
-      phase2_store((2 * i + 2) * 32, k0);                         // (dropped past the end)
-      phase3(lds + s_cur + HALF, k1);                             // tile 2i+1
-      const int t = s_cur; s_cur = s_nxt; s_nxt = s_far; s_far = t;
-    }
+    // after this barrier nobody reads the step before tp / 2 any more (tp even): its slot takes step tp / 2 + 2
+    if (!(tp & 1)) issue((tp >> 1) + 2);
   }
+  wait_vmem<0>();                                             // (copies past the end: zeros, no traffic)
 
   // ---- dk = scale * dK^T transposed, dv = dV^T transposed: 4 consecutive head-dim values per register group
   if (key < p.S) {
@@ -494,16 +502,16 @@ hipError_t attention_fwd(int batch, int n_heads, int seq, int head_dim, int caus
 }
 
 template <int DH>
-static hipError_t launch_bwd_kv(const AttnBwdParams& p, hipStream_t s) {
-  constexpr size_t smem = 3 * (2 * 64 * DH * 2 + 1024);
-  auto kern = attn_bwd_kv_kernel<DH>;
+static hipError_t launch_bwd_kv_split(const AttnBwdParams& p, hipStream_t s) {
+  constexpr size_t smem = 3 * (2 * 64 * DH * 2 + 1024) + 2 * 4 * 4096;      // three slots + two hand-over buffers
+  auto kern = attn_bwd_kv_split_kernel<DH>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)(p.H * p.B), (unsigned)((p.S + 127) / 128)), dim3(256), smem, s, p);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(p.H * p.B), (unsigned)((p.S + 127) / 128)), dim3(512), smem, s, p);
   return hipGetLastError();
 }
 
@@ -520,8 +528,8 @@ hipError_t attention_p1(int batch, int n_heads, int seq, int head_dim, int causa
   p.B = batch; p.H = n_heads; p.S = seq; p.causal = causal;
   p.scale = 1.f / sqrtf((float)head_dim);
   p.scale_log2e = 1.4426950408889634f * p.scale;
-  if (head_dim == 128) e = launch_bwd_kv<128>(p, s);
-  else if (head_dim == 64) e = launch_bwd_kv<64>(p, s);
+  if (head_dim == 128) e = launch_bwd_kv_split<128>(p, s);
+  else if (head_dim == 64) e = launch_bwd_kv_split<64>(p, s);
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
   // dq = scale * dS k = scale * (dS^T)^T k per (sequence, head): contraction over keys, causal: keys <= query

@@ -54,6 +54,13 @@ __device__ __forceinline__ void dma4(uint32_t lds_base, u32x4 desc, uint32_t vof
                :: "s"(lds_base), "v"(voff), "s"(desc) : "memory");
 }
 
+// Store of 8 bytes per lane that the compiler does not track: a workgroup barrier after it then does not wait for the
+// write to be acknowledged (the compiler's barrier waits for every vector-memory operation it knows to be in flight).
+// For data that nobody reads before the kernel ends.  soff is wave-uniform.
+__device__ __forceinline__ void store8_async(u32x2 data, u32x4 desc, uint32_t voff, uint32_t soff) {
+  asm volatile("buffer_store_dwordx2 %0, %1, %2, %3 offen" :: "v"(data), "v"(voff), "s"(desc), "s"(soff) : "memory");
+}
+
 template <int N> __device__ __forceinline__ void wait_vmem() {   // at most N vector-memory operations outstanding
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
 }
