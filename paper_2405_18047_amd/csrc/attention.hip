@@ -321,7 +321,19 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
       }
     }
     const u32x4 rst = make_desc(p.dst + bh * p.S * p.S, (uint32_t)((long)p.S * p.S * 2));
-    const unsigned st_off = key < p.S ? (unsigned)(((long)key * p.S + 4 * g) * 2) : kOob;
+    // The tile of dS^T (32 keys x 32 queries) leaves through a per-wave LDS buffer (rows padded to 80 bytes against bank
+    // conflicts): a lane holds 4 consecutive queries of its key row per register group, which stored directly is 8 bytes
+    // per lane and 32 rows per instruction; read back row-major it is 16 bytes per lane, 64 contiguous bytes per key row
+    // and 16 rows per instruction.
+    constexpr int STG_ROW = 80;
+    lds_u8* const stg = hand + 2 * HAND + wave * (32 * STG_ROW);
+    lds_u8* const stg_wr = stg + kl * STG_ROW + 8 * g;          // + 16 e4
+    unsigned st_row[2];
+#pragma unroll
+    for (int r = 0; r < 2; r++) {
+      const int row = (lane + 64 * r) >> 2;
+      st_row[r] = kw0 + row < p.S ? (unsigned)(((long)(kw0 + row) * p.S + 8 * (lane & 3)) * 2) : kOob;
+    }
     __syncthreads();                                          // steps step0 and step0 + 1 have landed (right waves waited)
     for (int it = 0; it <= nt; it++) {
       if (it < nt) {
@@ -375,8 +387,14 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
         const u32x4 s0 = __builtin_bit_cast(u32x4, ks[0]), s1 = __builtin_bit_cast(u32x4, ks[1]);
         const u32x2 dsv[4] = {u32x2{s0[0], s0[1]}, u32x2{s0[2], s0[3]}, u32x2{s1[0], s1[1]}, u32x2{s1[2], s1[3]}};
 #pragma unroll
-        for (int e4 = 0; e4 < 4; e4++)
-          store8_async(dsv[e4], rst, qt0 + 8 * e4 < p.S ? st_off : kOob, (uint32_t)__builtin_amdgcn_readfirstlane((qt0 + 8 * e4) * 2));
+        for (int e4 = 0; e4 < 4; e4++) *reinterpret_cast<LDS_AS u32x2*>(stg_wr + 16 * e4) = dsv[e4];
+        // (LDS operations of a wave execute in order: the reads below see the writes above)
+#pragma unroll
+        for (int r = 0; r < 2; r++) {
+          const int idx = lane + 64 * r;
+          const u32x4 v = *reinterpret_cast<const LDS_AS u32x4*>(stg + (idx >> 2) * STG_ROW + 16 * (idx & 3));
+          store16_async(v, rst, qt0 + 8 * (lane & 3) < p.S ? st_row[r] : kOob, (uint32_t)__builtin_amdgcn_readfirstlane(qt0 * 2));
+        }
       }
       __syncthreads();
     }
@@ -414,11 +432,24 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
     const unsigned off = (live && wave < 2 && q < p.S) ? (unsigned)((wave & 1) == 0 ? q * 4 : (long)q * p.H * 4) : kOob;
     dma4(slot + 2 * IMG + wave * 256, ds, off);
   };
-  f32x16 dvt[DT], dkt[DT];
+  // A right wave owns 32 head-dim columns (its index) of dV^T and dK^T for all four key blocks of the workgroup: it then
+  // reads only its quarter of the Q and dO tiles as transposed fragments (the expensive reads) and all four left waves'
+  // P and dS (cheap, lane-contiguous).  With head_dim 64 waves 2 and 3 have no columns and only copy.
+  f32x16 dvt[4], dkt[4];
 #pragma unroll
-  for (int t = 0; t < DT; t++)
+  for (int t = 0; t < 4; t++)
 #pragma unroll
     for (int e = 0; e < 16; e++) { dvt[t][e] = 0.f; dkt[t][e] = 0.f; }
+  const bool has_cols = wave < DT;
+  int col0 = 0, col1 = 0;                                     // fragment offsets of this wave's column block
+#pragma unroll
+  for (int t = 0; t < DT; t++)
+    if (t == wave) { col0 = fo.cols[t][0]; col1 = fo.cols[t][1]; }
+  auto my_cols = [&](lds_u8* img, int u) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s16x4*>(img + col0 + 16 * u * HT::RB));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s16x4*>(img + col1 + 16 * u * HT::RB));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
 
   issue(step0);
   issue(step0 + 1);
@@ -426,28 +457,27 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
   __syncthreads();
   for (int it = 0; it <= nt; it++) {
     const int tp = t0 + it;                                   // the tile the left waves are on
-    if (it > 0) {
+    if (it > 0 && has_cols) {
       const int tile = tp - 1;
       lds_u8* const qimg = lds + ((tile >> 1) % 3) * SLOT + (tile & 1) * HALF;
       lds_u8* const dimg = qimg + IMG;
-      const lds_u8* const in = my_hand + (tile & 1) * HAND;
-      bf16x8 kp[2], ks[2];
-      kp[0] = *reinterpret_cast<const LDS_AS bf16x8*>(in);
-      kp[1] = *reinterpret_cast<const LDS_AS bf16x8*>(in + 1024);
-      ks[0] = *reinterpret_cast<const LDS_AS bf16x8*>(in + 2048);
-      ks[1] = *reinterpret_cast<const LDS_AS bf16x8*>(in + 3072);
-      constexpr int N = 2 * DT, PF = N < 3 ? N : 3;           // (u, t) pairs; fragments requested PF pairs ahead
-      bf16x8 fo_d[N], fo_q[N];
+      // this wave's 32 head-dim columns of dO^T and Q^T (two k-steps of 16 queries), then every key block's P and dS
+      bf16x8 fo_d[2], fo_q[2];
 #pragma unroll
-      for (int j = 0; j < PF; j++) { fo_d[j] = HT::cols_frag(dimg, fo, 0, j / DT, j % DT); fo_q[j] = HT::cols_frag(qimg, fo, 0, j / DT, j % DT); }
+      for (int u = 0; u < 2; u++) { fo_d[u] = my_cols(dimg, u); fo_q[u] = my_cols(qimg, u); }
+      const lds_u8* const in = hand + (tile & 1) * HAND + lane * 16;
 #pragma unroll
-      for (int j = 0; j < N; j++) {
-        if (j + PF < N) {
-          fo_d[j + PF] = HT::cols_frag(dimg, fo, 0, (j + PF) / DT, (j + PF) % DT);
-          fo_q[j + PF] = HT::cols_frag(qimg, fo, 0, (j + PF) / DT, (j + PF) % DT);
+      for (int kbk = 0; kbk < 4; kbk++) {
+        bf16x8 kp[2], ks[2];
+        kp[0] = *reinterpret_cast<const LDS_AS bf16x8*>(in + kbk * 4096);
+        kp[1] = *reinterpret_cast<const LDS_AS bf16x8*>(in + kbk * 4096 + 1024);
+        ks[0] = *reinterpret_cast<const LDS_AS bf16x8*>(in + kbk * 4096 + 2048);
+        ks[1] = *reinterpret_cast<const LDS_AS bf16x8*>(in + kbk * 4096 + 3072);
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+          dvt[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo_d[u], kp[u], dvt[kbk], 0, 0, 0);
+          dkt[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo_q[u], ks[u], dkt[kbk], 0, 0, 0);
         }
-        dvt[j % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo_d[j], kp[j / DT], dvt[j % DT], 0, 0, 0);
-        dkt[j % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo_q[j], ks[j / DT], dkt[j % DT], 0, 0, 0);
       }
     }
     // step (tp + 1) / 2 + 1 is what the left waves start two barriers from now, when tp is odd: it was issued three
@@ -460,18 +490,22 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
   wait_vmem<0>();                                             // (copies past the end: zeros, no traffic)
 
   // ---- dk = scale * dK^T transposed, dv = dV^T transposed: 4 consecutive head-dim values per register group
-  if (key < p.S) {
-    bf16_t* row = p.dqkv + (tok0 + key) * p.ld_dqkv + d + h * DH;
+  if (has_cols) {
 #pragma unroll
-    for (int t = 0; t < DT; t++)
+    for (int kbk = 0; kbk < 4; kbk++) {
+      const int krow = kv0 + 32 * kbk + kl;
+      if (krow < p.S) {
+        bf16_t* row = p.dqkv + (tok0 + krow) * p.ld_dqkv + d + h * DH + 32 * wave;
 #pragma unroll
-      for (int e4 = 0; e4 < 4; e4++) {
-        bf16x4 vk, vv;
+        for (int e4 = 0; e4 < 4; e4++) {
+          bf16x4 vk, vv;
 #pragma unroll
-        for (int r = 0; r < 4; r++) { vk[r] = (bf16_t)(dkt[t][4 * e4 + r] * p.scale); vv[r] = (bf16_t)dvt[t][4 * e4 + r]; }
-        *reinterpret_cast<bf16x4*>(row + 32 * t + 8 * e4 + 4 * g) = vk;
-        *reinterpret_cast<bf16x4*>(row + d + 32 * t + 8 * e4 + 4 * g) = vv;
+          for (int r = 0; r < 4; r++) { vk[r] = (bf16_t)(dkt[kbk][4 * e4 + r] * p.scale); vv[r] = (bf16_t)dvt[kbk][4 * e4 + r]; }
+          *reinterpret_cast<bf16x4*>(row + 8 * e4 + 4 * g) = vk;
+          *reinterpret_cast<bf16x4*>(row + d + 8 * e4 + 4 * g) = vv;
+        }
       }
+    }
   }
 }
 
@@ -503,7 +537,7 @@ hipError_t attention_fwd(int batch, int n_heads, int seq, int head_dim, int caus
 
 template <int DH>
 static hipError_t launch_bwd_kv_split(const AttnBwdParams& p, hipStream_t s) {
-  constexpr size_t smem = 3 * (2 * 64 * DH * 2 + 1024) + 2 * 4 * 4096;      // three slots + two hand-over buffers
+  constexpr size_t smem = 3 * (2 * 64 * DH * 2 + 1024) + 2 * 4 * 4096 + 4 * 32 * 80;     // three slots, two hand-over buffers, dS^T staging
   auto kern = attn_bwd_kv_split_kernel<DH>;
   static bool attr_set = false;
   if (!attr_set) {

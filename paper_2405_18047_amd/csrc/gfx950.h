@@ -61,6 +61,11 @@ __device__ __forceinline__ void store8_async(u32x2 data, u32x4 desc, uint32_t vo
   asm volatile("buffer_store_dwordx2 %0, %1, %2, %3 offen" :: "v"(data), "v"(voff), "s"(desc), "s"(soff) : "memory");
 }
 
+// The same with 16 bytes per lane.
+__device__ __forceinline__ void store16_async(u32x4 data, u32x4 desc, uint32_t voff, uint32_t soff) {
+  asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen" :: "v"(data), "v"(voff), "s"(desc), "s"(soff) : "memory");
+}
+
 template <int N> __device__ __forceinline__ void wait_vmem() {   // at most N vector-memory operations outstanding
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
 }
