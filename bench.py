@@ -471,8 +471,8 @@ def kernel_rates(shape, tbp, torch, dev, tdt) -> dict:
 
 
 def cpu_baseline(shape) -> dict:
-    """The CPU oracle as it stands, timed on ONE layer x ONE micro-batch of this workload's real layer shape
-    (forward, backward-p1, backward-p2), random inputs.  Reported baseline only."""
+    """The CPU oracle as it stands, timed on ONE layer x TWO micro-batches of this workload's real layer shape
+    (forward, backward-p1 of each, backward-p2 of both), random inputs: 10-20 s of CPU work.  Reported baseline only."""
     import numpy as np
     import oracle
     try:
@@ -480,7 +480,8 @@ def cpu_baseline(shape) -> dict:
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    one = shape.replace(n_layers=1, n_microbatches=1)
+    n_mb = 2
+    one = shape.replace(n_layers=1, n_microbatches=n_mb)
     rng = np.random.default_rng(shape.seed)
     d, f = shape.d_model, shape.d_ffn
     p = {"w_gu": [0.02 * rng.standard_normal((d, 2 * f))], "w_d": [0.02 * rng.standard_normal((f, d))],
@@ -488,18 +489,23 @@ def cpu_baseline(shape) -> dict:
     if shape.n_heads:
         p.update({"w_qkv": [0.02 * rng.standard_normal((d, 3 * d))], "w_o": [0.02 * rng.standard_normal((d, d))],
                   "g1": [1 + 0.02 * rng.standard_normal(d)]})
-    x = rng.standard_normal((shape.tokens, d))
-    dy = rng.standard_normal((shape.tokens, d))
+    xs = [rng.standard_normal((shape.tokens, d)) for _ in range(n_mb)]
+    dys = [rng.standard_normal((shape.tokens, d)) for _ in range(n_mb)]
     st = oracle.OracleStage(one, p)
-    t0 = time.perf_counter(); st.forward(0, x)
-    t1 = time.perf_counter(); st.backward_p1(0, dy)
-    t2 = time.perf_counter(); st.backward_p2([0])
+    t0 = time.perf_counter()
+    for m in range(n_mb):
+        st.forward(m, xs[m])
+    t1 = time.perf_counter()
+    for m in range(n_mb):
+        st.backward_p1(m, dys[m])
+    t2 = time.perf_counter()
+    st.backward_p2(range(n_mb))
     t3 = time.perf_counter()
     fl = p2_flops(one)
     return {"value": round(fl / (t3 - t2) / 1e12, 4), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"1 layer x 1 micro-batch of {shape.name} at the real layer shape, fp64 numpy; "
+            "sample": f"1 layer x {n_mb} micro-batches of {shape.name} at the real layer shape, fp64 numpy; "
                       f"fwd {t1 - t0:.2f} s, p1 {t2 - t1:.2f} s, p2 {t3 - t2:.2f} s",
-            "p1_ms_per_microbatch_extrapolated": round((t2 - t1) * 1e3 * shape.n_layers, 1)}
+            "p1_ms_per_microbatch_extrapolated": round((t2 - t1) * 1e3 / n_mb * shape.n_layers, 1)}
 
 
 if __name__ == "__main__":
