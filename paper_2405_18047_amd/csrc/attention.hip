@@ -307,19 +307,13 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
   const int t0 = 2 * step0, nt = 2 * (nstep - step0);         // first tile, number of tiles
   typedef LDS_AS float lds_f32;
   lds_u8* const my_hand = hand + wave * 4096 + lane * 16;     // + buffer * HAND + 1024 * {p0, p1, s0, s1}
+  constexpr int KVIMG = 128 * HT::RB;                         // image of the block's 128 K (then V) rows
+  lds_u8* const kvimg = lds + 2 * SLOT;
+  static_assert(2 * KVIMG <= SLOT + 2 * HAND, "K and V images must fit in the third slot plus the hand-over area");
 
   if (!right) {
     // ------------------------------------------------------------------ left: S, dP, P, dS, dS^T out
     bf16x8 kfb[KS], vfb[KS];
-    {
-      const __amdgpu_buffer_rsrc_t rk = make_rsrc(p.qkv + tok0 * p.ld_qkv + d + h * DH, (uint32_t)((long)p.S * p.ld_qkv * 2));
-      const unsigned off = key < p.S ? (unsigned)(((long)key * p.ld_qkv + 8 * g) * 2) : kOob;
-#pragma unroll
-      for (int s = 0; s < KS; s++) {
-        kfb[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, 32 * s, 0));
-        vfb[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rk, off, 32 * s + 2 * d, 0));
-      }
-    }
     const u32x4 rst = make_desc(p.dst + bh * p.S * p.S, (uint32_t)((long)p.S * p.S * 2));
     // The tile of dS^T (32 keys x 32 queries) leaves through a per-wave LDS buffer (rows padded to 80 bytes against bank
     // conflicts): a lane holds 4 consecutive queries of its key row per register group, which stored directly is 8 bytes
@@ -334,11 +328,19 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
       const int row = (lane + 64 * r) >> 2;
       st_row[r] = kw0 + row < p.S ? (unsigned)(((long)(kw0 + row) * p.S + 8 * (lane & 3)) * 2) : kOob;
     }
-    __syncthreads();                                          // steps step0 and step0 + 1 have landed (right waves waited)
+    __syncthreads();                                          // steps step0, step0 + 1 and the K / V rows have landed
+    // the lane's key row and value row as B operands (8 consecutive head-dim values per k-step), from the images the
+    // right waves copied into the third slot and the hand-over area, which nothing else uses yet
+#pragma unroll
+    for (int s = 0; s < KS; s++) {
+      kfb[s] = HT::rows_frag(kvimg, fo, 32 * wave, s);
+      vfb[s] = HT::rows_frag(kvimg + KVIMG, fo, 32 * wave, s);
+    }
+    __syncthreads();                                          // every left wave has its rows: the area is free again
     for (int it = 0; it <= nt; it++) {
       if (it < nt) {
         const int tile = t0 + it, qt0 = tile * 32;
-        lds_u8* const slot = lds + ((tile >> 1) % 3) * SLOT;
+        lds_u8* const slot = lds + (((tile >> 1) - step0) % 3) * SLOT;
         lds_u8* const qimg = slot + (tile & 1) * HALF;
         lds_u8* const dimg = qimg + IMG;
         const lds_f32* const stat = reinterpret_cast<const lds_f32*>(slot + 2 * IMG) + 32 * (tile & 1);
@@ -398,6 +400,8 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
       }
       __syncthreads();
     }
+    __syncthreads();                                          // every right wave's copies have landed: the ring is free
+    __syncthreads();                                          // the right waves have put dK and dV into LDS (below)
     return;
   }
 
@@ -414,7 +418,7 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
   auto issue = [&](int i) {
     const int q0 = i * BQ;
     const bool live = i < nstep;
-    const uint32_t slot = lds0 + (i % 3) * SLOT;
+    const uint32_t slot = lds0 + ((i - step0) % 3) * SLOT;      // slots count from the block's first step
     const int qs = live ? q0 : 0;
     const u32x4 dq = make_desc(p.qkv + (tok0 + qs) * p.ld_qkv + h * DH, (uint32_t)((long)(p.S - qs) * p.ld_qkv * 2));
     const u32x4 dd = make_desc(p.dout + (tok0 + qs) * p.ld_do + h * DH, (uint32_t)((long)(p.S - qs) * p.ld_do * 2));
@@ -451,15 +455,29 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
 
+  {  // the block's K and V rows, for the left waves (coalesced here; fetched per lane they are 32-byte pieces of 32 rows)
+    const bf16_t* kb0 = p.qkv + (tok0 + kv0) * p.ld_qkv + d + h * DH;
+    const uint32_t bytes = (uint32_t)((long)(p.S - kv0) * p.ld_qkv * 2);
+    const u32x4 dk = make_desc(kb0, bytes), dv = make_desc(kb0 + d, bytes);
+#pragma unroll
+    for (int i = 0; i < 2 * NCH; i++) {
+      int row; unsigned go;
+      HT::plan(wave + 4 * i, lane, p.ld_qkv, row, go);
+      const unsigned off = kv0 + row < p.S ? go : kOob;
+      dma16(lds0 + 2 * SLOT + (wave + 4 * i) * 1024, dk, off);
+      dma16(lds0 + 2 * SLOT + KVIMG + (wave + 4 * i) * 1024, dv, off);
+    }
+  }
   issue(step0);
   issue(step0 + 1);
   wait_vmem<0>();
   __syncthreads();
+  __syncthreads();                                            // the left waves have read their K and V rows
   for (int it = 0; it <= nt; it++) {
     const int tp = t0 + it;                                   // the tile the left waves are on
     if (it > 0 && has_cols) {
       const int tile = tp - 1;
-      lds_u8* const qimg = lds + ((tile >> 1) % 3) * SLOT + (tile & 1) * HALF;
+      lds_u8* const qimg = lds + (((tile >> 1) - step0) % 3) * SLOT + (tile & 1) * HALF;
       lds_u8* const dimg = qimg + IMG;
       // this wave's 32 head-dim columns of dO^T and Q^T (two k-steps of 16 queries), then every key block's P and dS
       bf16x8 fo_d[2], fo_q[2];
@@ -488,22 +506,42 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
     if (!(tp & 1)) issue((tp >> 1) + 2);
   }
   wait_vmem<0>();                                             // (copies past the end: zeros, no traffic)
+  __syncthreads();                                            // ... of every wave, before the ring is reused below
 
-  // ---- dk = scale * dK^T transposed, dv = dV^T transposed: 4 consecutive head-dim values per register group
+  // ---- dk = scale * dK^T transposed, dv = dV^T transposed.  A lane holds 4 consecutive head-dim values of one key per
+  // register group; stored directly that is 8 bytes per lane scattered over 32 rows per instruction, and the 64 MB of
+  // dK and dV of a launch then cost a tenth of the kernel's time.  The waves put their column blocks together in LDS
+  // (the copy ring is free by now; rows padded to 272 bytes against bank conflicts) and each writes 32 whole key
+  // rows, 16 bytes per lane, 256 contiguous bytes per row.
+  constexpr int EROW = DH * 2 + 16;
+  lds_u8* const edk = lds;
+  lds_u8* const edv = lds + 128 * EROW;
+  static_assert(2 * 128 * EROW <= 3 * SLOT, "dK and dV tiles must fit in the ring");
   if (has_cols) {
 #pragma unroll
-    for (int kbk = 0; kbk < 4; kbk++) {
-      const int krow = kv0 + 32 * kbk + kl;
+    for (int kbk = 0; kbk < 4; kbk++)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; e4++) {
+        bf16x4 vk, vv;
+#pragma unroll
+        for (int r = 0; r < 4; r++) { vk[r] = (bf16_t)(dkt[kbk][4 * e4 + r] * p.scale); vv[r] = (bf16_t)dvt[kbk][4 * e4 + r]; }
+        const int off = (32 * kbk + kl) * EROW + (32 * wave + 8 * e4 + 4 * g) * 2;
+        *reinterpret_cast<LDS_AS bf16x4*>(edk + off) = vk;
+        *reinterpret_cast<LDS_AS bf16x4*>(edv + off) = vv;
+      }
+  }
+  __syncthreads();
+  {
+    constexpr int LPR = DH / 8, RPI = 64 / LPR;               // lanes per row, rows per wave-wide store
+    const int rl = lane / LPR, piece = lane % LPR;
+#pragma unroll
+    for (int r0 = 0; r0 < 32; r0 += RPI) {
+      const int row = 32 * wave + r0 + rl;                    // this wave's 32 key rows
+      const int krow = kv0 + row;
       if (krow < p.S) {
-        bf16_t* row = p.dqkv + (tok0 + krow) * p.ld_dqkv + d + h * DH + 32 * wave;
-#pragma unroll
-        for (int e4 = 0; e4 < 4; e4++) {
-          bf16x4 vk, vv;
-#pragma unroll
-          for (int r = 0; r < 4; r++) { vk[r] = (bf16_t)(dkt[kbk][4 * e4 + r] * p.scale); vv[r] = (bf16_t)dvt[kbk][4 * e4 + r]; }
-          *reinterpret_cast<bf16x4*>(row + 8 * e4 + 4 * g) = vk;
-          *reinterpret_cast<bf16x4*>(row + d + 8 * e4 + 4 * g) = vv;
-        }
+        bf16_t* const out = p.dqkv + (tok0 + krow) * p.ld_dqkv + d + h * DH + 8 * piece;
+        *reinterpret_cast<u32x4*>(out) = *reinterpret_cast<const LDS_AS u32x4*>(edk + row * EROW + 16 * piece);
+        *reinterpret_cast<u32x4*>(out + d) = *reinterpret_cast<const LDS_AS u32x4*>(edv + row * EROW + 16 * piece);
       }
     }
   }
