@@ -109,20 +109,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int d = p.H * DH;
   const long tok0 = (long)b * p.S;
 
-  // ---- this lane's query row as B operand of S^T = K Q^T: 8 consecutive head-dim values per k-step
-  bf16x8 qf[KS];
-  {
-    const __amdgpu_buffer_rsrc_t dq = make_rsrc(p.qkv + tok0 * p.ld_qkv + h * DH, (uint32_t)((long)p.S * p.ld_qkv * 2));
-    const unsigned off = query < p.S ? (unsigned)(((long)query * p.ld_qkv + 8 * g) * 2) : kOob;
-#pragma unroll
-    for (int s = 0; s < KS; s++)
-      qf[s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(dq, off, 32 * s, 0));
-  }
-  // complete here: the compiler's own wait for these registers would otherwise sit inside the loop and, the counter
-  // being in order, also wait for the asynchronous copies issued after them
-  wait_vmem<0>();
-
   const typename HT::Offsets fo = HT::offsets(lane);
+  // ---- the block's 128 query rows: copied (coalesced) into the second slot, which the loop fills only after its first
+  // barrier; fetched per lane they would be 32-byte pieces of 32 rows per instruction
+  {
+    const u32x4 dq = make_desc(p.qkv + (tok0 + q0) * p.ld_qkv + h * DH, (uint32_t)((long)(p.S - q0) * p.ld_qkv * 2));
+#pragma unroll
+    for (int i = 0; i < 2 * NCH; i++) {
+      int row; unsigned go;
+      HT::plan(wave + 4 * i, lane, p.ld_qkv, row, go);
+      dma16(lds0 + SLOT + (wave + 4 * i) * 1024, dq, q0 + row < p.S ? go : kOob);
+    }
+  }
   // ---- copy plan of this wave: chunks wave, wave + 4, ... of the K image and of the V image
   int c_row[NCH];
   unsigned c_off[NCH];
@@ -152,9 +150,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   float m = -INFINITY, l = 0.f;
 
   issue(0);
+  wait_vmem<0>();
+  __syncthreads();
+  // ---- this lane's query row as B operand of S^T = K Q^T: 8 consecutive head-dim values per k-step
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int s = 0; s < KS; s++) qf[s] = HT::rows_frag(lds + SLOT, fo, 32 * wave, s);
   for (int j = 0; j < nblk; j++) {
     wait_vmem<0>();
-    __syncthreads();                   // block j has landed; every wave is done with the other slot
+    __syncthreads();                   // block j has landed; every wave is done with the other slot (and has its query row)
     if (j + 1 < nblk) issue(j + 1);
     const int kv0 = j * BKV;
     if (p.causal && kv0 > qw0 + 31) continue;          // every key of the block is after every query of this wave
@@ -231,10 +235,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
   }
 
-  // ---- o = O^T / l, transposed back on the way out: a lane holds 4 consecutive head-dim values per register group
-  if (query < p.S) {
+  // ---- o = O^T / l, transposed back on the way out.  A lane holds 4 consecutive head-dim values of its query per
+  // register group (8 bytes, 32 rows per instruction if stored directly): each wave passes its 32 rows through LDS
+  // (the ring is free after one more barrier; rows padded to DH * 2 + 16 bytes against bank conflicts) and writes them
+  // whole, 16 bytes per lane.
+  __syncthreads();
+  constexpr int EROW = DH * 2 + 16;
+  static_assert(128 * EROW <= 2 * SLOT, "the output tile must fit in the ring");
+  lds_u8* const erow = lds + 32 * wave * EROW;
+  {
     const float inv = 1.f / l;
-    bf16_t* orow = p.out + (tok0 + query) * p.ld_out + h * DH;
 #pragma unroll
     for (int t = 0; t < DT; t++)
 #pragma unroll
@@ -242,9 +252,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         bf16x4 v;
 #pragma unroll
         for (int r = 0; r < 4; r++) v[r] = (bf16_t)(ot[t][4 * e4 + r] * inv);
-        *reinterpret_cast<bf16x4*>(orow + 32 * t + 8 * e4 + 4 * g) = v;
+        *reinterpret_cast<LDS_AS bf16x4*>(erow + ql * EROW + (32 * t + 8 * e4 + 4 * g) * 2) = v;
       }
-    if (g == 0) p.lse[((long)b * p.H + h) * p.S + query] = m + __builtin_amdgcn_logf(l);
+    if (g == 0 && query < p.S) p.lse[((long)b * p.H + h) * p.S + query] = m + __builtin_amdgcn_logf(l);
+  }
+  {  // (LDS operations of a wave execute in order: the reads below see this wave's own writes above)
+    constexpr int LPR = DH / 8, RPI = 64 / LPR;
+    const int rl = lane / LPR, piece = lane % LPR;
+#pragma unroll
+    for (int r0 = 0; r0 < 32; r0 += RPI) {
+      const int qrow = qw0 + r0 + rl;
+      if (qrow < p.S)
+        *reinterpret_cast<u32x4*>(p.out + (tok0 + qrow) * p.ld_out + h * DH + 8 * piece) =
+            *reinterpret_cast<const LDS_AS u32x4*>(erow + (r0 + rl) * EROW + 16 * piece);
+    }
   }
 }
 
