@@ -282,7 +282,7 @@ struct AttnBwdParams {
   const float* lse;                    // [B, H, S] from the forward
   const float* delta;                  // [B*S, H]: rowsum(dout * out) per (token, head)
   bf16_t* dqkv; long ld_dqkv;          // dk and dv blocks are written (columns H*DH.. and 2*H*DH..)
-  bf16_t* dst;                         // [B, H, S(key), S(query)] = dS^T
+  bf16_t* dst;                         // dS^T per (b, h) in panels of 128 queries: [ceil(S / 128)][S keys][128 queries]
   int B, H, S, causal;
   float scale, scale_log2e;
 };
@@ -335,7 +335,8 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
   if (!right) {
     // ------------------------------------------------------------------ left: S, dP, P, dS, dS^T out
     bf16x8 kfb[KS], vfb[KS];
-    const u32x4 rst = make_desc(p.dst + bh * p.S * p.S, (uint32_t)((long)p.S * p.S * 2));
+    const long ds_elems = (long)attn_ds_elems(p.S);
+    const u32x4 rst = make_desc(p.dst + bh * ds_elems, (uint32_t)(ds_elems * 2));
     // The tile of dS^T (32 keys x 32 queries) leaves through a per-wave LDS buffer (rows padded to 80 bytes against bank
     // conflicts): a lane holds 4 consecutive queries of its key row per register group, which stored directly is 8 bytes
     // per lane and 32 rows per instruction; read back row-major it is 16 bytes per lane, 64 contiguous bytes per key row
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
 #pragma unroll
     for (int r = 0; r < 2; r++) {
       const int row = (lane + 64 * r) >> 2;
-      st_row[r] = kw0 + row < p.S ? (unsigned)(((long)(kw0 + row) * p.S + 8 * (lane & 3)) * 2) : kOob;
+      st_row[r] = kw0 + row < p.S ? (unsigned)(((kw0 + row) * kPanel + 8 * (lane & 3)) * 2) : kOob;
     }
     __syncthreads();                                          // steps step0, step0 + 1 and the K / V rows have landed
     // the lane's key row and value row as B operands (8 consecutive head-dim values per k-step), from the images the
@@ -416,7 +417,9 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
         for (int r = 0; r < 2; r++) {
           const int idx = lane + 64 * r;
           const u32x4 v = *reinterpret_cast<const LDS_AS u32x4*>(stg + (idx >> 2) * STG_ROW + 16 * (idx & 3));
-          store16_async(v, rst, qt0 + 8 * (lane & 3) < p.S ? st_row[r] : kOob, (uint32_t)__builtin_amdgcn_readfirstlane(qt0 * 2));
+          // panel qt0 / 128 starts at (qt0 / 128) * S * 128 elements; the tile's queries are columns qt0 % 128 .. + 31 of it
+          const long pan = ((long)(qt0 / kPanel) * p.S * kPanel + qt0 % kPanel) * 2;
+          store16_async(v, rst, qt0 + 8 * (lane & 3) < p.S ? st_row[r] : kOob, (uint32_t)__builtin_amdgcn_readfirstlane((int)pan));
         }
       }
       __syncthreads();
@@ -627,10 +630,11 @@ hipError_t attention_p1(int batch, int n_heads, int seq, int head_dim, int causa
   if (e != hipSuccess) return e;
   // dq = scale * dS k = scale * (dS^T)^T k per (sequence, head): contraction over keys, causal: keys <= query
   const long d = (long)n_heads * head_dim;
-  GemmArgs g = gemm_args(TN, seq, head_dim, seq, ds_t, seq, (const char*)qkv + d * 2, ld_qkv, dqkv, ld_dqkv);
+  GemmArgs g = gemm_args(TN, seq, head_dim, seq, ds_t, kPanel, (const char*)qkv + d * 2, ld_qkv, dqkv, ld_dqkv);
   g.alpha = p.scale;
+  g.a_panel = (long)seq * kPanel;
   g.batch = batch * n_heads; g.batch_inner = n_heads;
-  g.sAo = (long)n_heads * seq * seq; g.sAi = (long)seq * seq;
+  g.sAi = (long)attn_ds_elems(seq); g.sAo = n_heads * g.sAi;
   g.sBo = (long)seq * ld_qkv; g.sBi = head_dim;
   g.sCo = (long)seq * ld_dqkv; g.sCi = head_dim;
   g.causal = causal ? CAUSAL_K_END : CAUSAL_NONE;

@@ -34,6 +34,7 @@ struct GemmParams {
   // fused softmax backward (see GemmArgs)
   const float* delta; long ldd, sDo, sDi;
   int delta_causal;
+  long a_panel;                 // see GemmArgs
   // contraction split over `split` workgroups per tile (see SplitPlan)
   int split;
   float* split_ws;
@@ -191,7 +192,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   for (int i = 0; i < NA; i++) TA::copy_plan(wave + 4 * i, lane, p.lda, m0, p.M, a_goff[i], a_kidx[i]);
 #pragma unroll
   for (int i = 0; i < NB; i++) TB::copy_plan(wave + 4 * i, lane, p.ldb, n0, p.N, b_goff[i], b_kidx[i]);
-  const bf16_t* Ablk = AKC ? A + (long)m0 * p.lda : A + m0;     // tile origin at k = 0
+  // tile origin at k = 0 (an operand stored in panels is only ever given to the kernel whose BM is the panel width)
+  const bf16_t* Ablk = AKC ? A + (long)m0 * p.lda : (p.a_panel ? A + (long)tm_i * p.a_panel : A + m0);
   const bf16_t* Bblk = BKC ? B + (long)n0 * p.ldb : B + n0;
   const long a_kstep = AKC ? 1 : p.lda;                          // elements per unit of k
   const long b_kstep = BKC ? 1 : p.ldb;
@@ -488,15 +490,27 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
 
 template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
-  int tm_i, tn_i;
+  int tm_i, tn_i, z = (int)blockIdx.z;
   if (gridDim.z == 1) {
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tm_i, tn_i);
   } else {
-    // Batched (per-head) products: the causal variants do an amount of work that depends on the tile row, and the
-    // hardware hands consecutive workgroup ids to the 8 XCDs in turn, so a fixed id -> tile map would give one XCD
-    // all the long tiles of every head.  Rotating the map by the batch index spreads them evenly.
+    // Batched (per-head) products.  The hardware hands consecutive workgroup ids (x fastest, then z) to the 8 XCDs in
+    // turn, and each XCD has its own L2: with the plain id -> (tile, batch entry) map the tiles of one batch entry,
+    // which share its operands, would be spread over all 8 XCDs and every L2 would fetch those operands again.  When
+    // the batch count is a multiple of 8 the map is therefore regrouped so that an XCD walks whole batch entries; a
+    // causal contraction that grows with the tile row starts with the longest tiles of each entry.
     const int nt = (int)gridDim.x;
-    int id = ((int)blockIdx.x + 3 * (int)blockIdx.z) % nt;
+    int id;
+    if ((gridDim.z & 7) == 0) {
+      const int lin = (int)blockIdx.x + nt * (int)blockIdx.z;
+      const int xcd = lin & 7, j = lin >> 3;
+      z = xcd + 8 * (j / nt);
+      id = j % nt;
+      if (p.causal == CAUSAL_K_END) id = nt - 1 - id;
+    } else {
+      // otherwise rotating the map by the batch index at least keeps one XCD from getting all the long tiles
+      id = ((int)blockIdx.x + 3 * z) % nt;
+    }
     if (p.causal == CAUSAL_SKIP_UPPER && p.tiles_m == p.tiles_n) {
       // only the lower-triangular tiles are launched: id = tm (tm + 1) / 2 + tn
       tm_i = (int)((__builtin_sqrtf(8.f * (float)id + 1.f) - 1.f) * 0.5f);
@@ -508,7 +522,28 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
       tn_i = id / p.tiles_m;
     }
   }
-  gemm_bf16_tile<BM, BN, AKC, BKC, OutT, KD>(p, tm_i, tn_i, (int)blockIdx.z);
+  gemm_bf16_tile<BM, BN, AKC, BKC, OutT, KD>(p, tm_i, tn_i, z);
+}
+
+// Batched product with a causal contraction end (rows of tile i contract over (i + 1) * BM indices) and one tile column:
+// a workgroup takes tile nt - 1 - i and then tile i, so every workgroup does the same amount of work, nt + 1 units,
+// there are half as many of them (each pays its start-up once per two tiles' worth of streaming) and no compute unit
+// is left with a long tile at the end.  Batch entries are regrouped by XCD as in gemm_bf16_kernel.
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD>
+__global__ __launch_bounds__(256) void gemm_bf16_causal_pair_kernel(GemmParams p) {
+  const int np = (int)gridDim.x, nt = p.tiles_m;              // np = ceil(nt / 2) workgroups per batch entry
+  int z = (int)blockIdx.z, id = (int)blockIdx.x;
+  if ((gridDim.z & 7) == 0) {
+    const int lin = (int)blockIdx.x + np * (int)blockIdx.z;
+    const int xcd = lin & 7, j = lin >> 3;
+    z = xcd + 8 * (j / np);
+    id = j % np;
+  }
+  const int reps = (nt - 1 - id > id) ? 2 : 1;                // the middle tile of an odd count stands alone
+  for (int r = 0; r < reps; r++) {
+    gemm_bf16_tile<BM, BN, AKC, BKC, OutT, KD>(p, r == 0 ? nt - 1 - id : id, 0, z);
+    __syncthreads();                          // every wave has read its strip back: the ring may be refilled
+  }
 }
 
 // `split` workgroups per output tile, each over its slice of the contraction.  The hardware hands consecutive
@@ -707,6 +742,25 @@ static hipError_t launch_bf16(const GemmParams& p0, int batch, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD>
+static hipError_t launch_bf16_causal_pair(const GemmParams& p0, int batch, hipStream_t s) {
+  GemmParams p = p0;
+  p.tiles_m = (p.M + BM - 1) / BM;
+  p.tiles_n = (p.N + BN - 1) / BN;
+  if (p.tiles_n != 1 || p.causal != CAUSAL_K_END) return hipErrorInvalidValue;
+  constexpr size_t smem = (size_t)(KD == 32 ? STAGES : 2) * (BM + BN) * KD * sizeof(bf16_t);
+  auto kern = gemm_bf16_causal_pair_kernel<BM, BN, AKC, BKC, OutT, KD>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)((p.tiles_m + 1) / 2), 1, (unsigned)batch), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
 // Tiles 192 columns wide for the linear-layer products whose output fills the chip badly with 256 x 256 tiles (too
 // few of them, or a last round that is mostly empty): e.g. [2048, 5120] is 160 large tiles (62 % of a round) but 216
 // of the narrower ones (84 %).  Taken when the fraction of the rounds' capacity that is useful output, discounted
@@ -831,6 +885,7 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
   p.alpha = g.alpha; p.accumulate = g.accumulate; p.causal = g.causal;
   p.delta = g.delta; p.ldd = g.ldd; p.sDo = g.sDo; p.sDi = g.sDi; p.delta_causal = g.delta_causal;
   if (dtype == 0) {
+    if (g.a_panel) return hipErrorInvalidValue;
     switch (g.layout) {
       case NN: p.sam = g.lda; p.sak = 1; p.sbk = g.ldb; p.sbn = 1; break;
       case NT: p.sam = g.lda; p.sak = 1; p.sbk = 1; p.sbn = g.ldb; break;
@@ -842,6 +897,16 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)g.batch);
     hipLaunchKernelGGL(gemm_f32_kernel<float>, grid, dim3(256), 0, s, p);   // fp32 storage: C is fp32 either way
     return hipGetLastError();
+  }
+  if (g.a_panel) {
+    if (g.layout != TN || g.lda != kPanel || g.ws) return hipErrorInvalidValue;
+    p.a_panel = g.a_panel;
+    // (pairs only when they still give every compute unit its two workgroups)
+    if (!g.out_f32 && g.causal == CAUSAL_K_END && g.N <= 128 && !g.delta &&
+        (long)((g.M + kPanel - 1) / kPanel + 1) / 2 * g.batch >= 512)
+      return launch_bf16_causal_pair<kPanel, 128, false, false, bf16_t, 32>(p, g.batch, s);
+    return g.out_f32 ? launch_bf16<kPanel, 128, false, false, float, 32>(p, g.batch, s)
+                     : launch_bf16<kPanel, 128, false, false, bf16_t, 32>(p, g.batch, s);
   }
   // bf16: large tiles when the output is big enough to fill 256 compute units with them
   const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;

@@ -45,7 +45,14 @@ struct GemmArgs {
   // ws_counters_zero = 0 makes gemm() clear them first (a small fill launch).
   void* ws; size_t ws_bytes;
   int ws_counters_zero;
+  // TN layout, storage-type operands only: A is stored in panels of kPanel output rows, element (k, m) at
+  // A[(m / kPanel) * a_panel + k * lda + m % kPanel] with lda == kPanel, so that the K x kPanel slab an output tile
+  // contracts over is one contiguous stream.  0: plain [K, lda] matrix.  Such a product runs on kPanel-wide tiles.
+  long a_panel;
 };
+constexpr int kPanel = 128;
+// elements of one (sequence, head) entry of the fused attention's dS^T scratch, stored in such panels
+constexpr size_t attn_ds_elems(int seq) { return (size_t)((seq + kPanel - 1) / kPanel) * seq * kPanel; }
 
 // Split of the contraction over several workgroups per output tile.  An output with fewer than 192 tiles of
 // 256 x 256 leaves compute units idle (or falls back to small tiles that move twice the operand bytes per FLOP);
@@ -115,7 +122,8 @@ hipError_t attention_fwd(int batch, int n_heads, int seq, int head_dim, int caus
 
 // Backward-p1 of the same: dq, dk, dv into the column blocks of dqkv from qkv, the forward's output and lse and the
 // output derivative d_out (dense rows: ld_out == n_heads*head_dim).  delta: scratch [batch*seq, n_heads] fp32;
-// ds_t: scratch [batch, n_heads, seq, seq] storage type (receives dS^T).
+// ds_t: scratch of batch * n_heads * attn_ds_elems(seq) storage-type elements (receives dS^T in panels of kPanel
+// queries: per (sequence, head) [ceil(seq / kPanel)][seq keys][kPanel queries]).
 hipError_t attention_p1(int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv, long ld_qkv,
                         const void* out, const void* d_out, long ld_out, const float* lse, void* dqkv, long ld_dqkv,
                         float* delta, void* ds_t, hipStream_t s);

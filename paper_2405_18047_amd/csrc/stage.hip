@@ -116,7 +116,8 @@ Layout plan(const Dims& c) {
   y.ws_t_d0 = off; off += align_up((size_t)c.T * c.d * c.e, 256);
   y.ws_t_d1 = off; off += align_up((size_t)c.T * c.d * c.e, 256);
   // fp32 scores, then dS (materialised attention) or dS^T in the storage type (fused)
-  y.ws_scores = off; off += c.attn ? align_up((size_t)c.B * c.H * c.S * c.S * (c.fused ? c.e : sizeof(float)), 256) : 0;
+  y.ws_scores = off; off += !c.attn ? 0 : align_up(c.fused ? (size_t)c.B * c.H * tbp::attn_ds_elems(c.S) * c.e
+                                                           : (size_t)c.B * c.H * c.S * c.S * sizeof(float), 256);
   y.ws_norm_partials = off; off += align_up((size_t)tbp::kNormPartialBlocks * c.d * sizeof(float), 256);
   y.ws_norm_partials_p2 = off; off += c.literal ? align_up((size_t)tbp::kNormPartialBlocks * c.d * sizeof(float), 256) : 0;
   y.ws_rope = off; off += c.attn ? align_up((size_t)c.S * (c.dh / 2) * sizeof(float2), 256) : 0;
@@ -702,7 +703,7 @@ tbp_status tbp_attention_fwd(int dtype, int batch, int n_heads, int seq, int hea
 
 size_t tbp_attention_p1_scratch_bytes(int batch, int n_heads, int seq) {
   if (batch <= 0 || n_heads <= 0 || seq <= 0) return 0;
-  return align_up((size_t)batch * seq * n_heads * sizeof(float), 256) + (size_t)batch * n_heads * seq * seq * 2;
+  return align_up((size_t)batch * seq * n_heads * sizeof(float), 256) + (size_t)batch * n_heads * tbp::attn_ds_elems(seq) * 2;
 }
 
 tbp_status tbp_attention_p1(int dtype, int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv,
