@@ -198,9 +198,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int e = 0; e < 16; e++) mx = fmaxf(mx, st[kt][e]);
     mx = fmaxf(mx, xor32(mx)) * p.scale_log2e;          // scale > 0: the maximum commutes with it
+    // The reference point m of the exponentials only has to stay within a safe distance of the running maximum, not
+    // on it: o / l and lse = m + log2 l are the same for any m.  It is moved (and what is accumulated rescaled) only
+    // when some query's maximum has risen by more than kSlack octaves above it; until then p <= 2^kSlack, far inside
+    // the range of fp32 sums and of the storage type.  With the maximum itself as reference nearly every block moves
+    // some lane's maximum and pays 16 * DT multiplications per lane; this way typically only the first block does.
+    constexpr float kSlack = 8.f;
     const float mnew = fmaxf(m, mx);
-    if (__any(mnew != m)) {                           // some query's maximum moved: rescale what is accumulated
-      const float alpha = __builtin_amdgcn_exp2f(m - mnew);    // first block: exp2(-inf) = 0
+    if (__any(mnew > m + kSlack)) {
+      const float alpha = __builtin_amdgcn_exp2f(m - mnew);    // first block: m = -inf, exp2(-inf) = 0
       l *= alpha;
 #pragma unroll
       for (int t = 0; t < DT; t++)

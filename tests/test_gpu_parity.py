@@ -257,6 +257,30 @@ def test_fused_attention_forward(seq, nb, H, dh, causal):
             assert np.max(np.abs(got[b, h] - ref)) < 2e-3 * max(1.0, np.max(np.abs(ref)))
 
 
+@pytest.mark.parametrize("gain", [6.0, 0.05])
+def test_fused_attention_forward_score_range(gain):
+    """The forward kernel keeps the reference point of its exponentials within a fixed distance of the running row
+    maximum instead of on it.  Large scores (the maximum climbs by many octaves along the row, so the reference point
+    moves several times) and tiny ones (it never moves after the first block) must give the oracle's output and row
+    log-sum-exp all the same."""
+    seq, nb, H, dh = 640, 1, 2, 128
+    _say(f"attention fwd score range gain={gain}")
+    d = H * dh
+    q = _rnd(43, "q", (nb * seq, d), "bf16", scale=gain)
+    k, v = (_rnd(43, n, (nb * seq, d), "bf16") for n in ("k", "v"))
+    o_ref, P = ops.attention_fwd(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), seq, H, dh, True)
+    qkv = to_dev(np.concatenate([q, k, v], axis=1), "bf16")
+    out, lse2 = tbp.tbp_attention_fwd(qkv, seq, H, dh, True)
+    assert max_rel(to_np(out), o_ref) < 1e-2
+    got = to_np(lse2) * np.log(2.0)
+    for h in range(H):
+        s = (q[:, h * dh:(h + 1) * dh].astype(np.float64) @ k[:, h * dh:(h + 1) * dh].astype(np.float64).T) / np.sqrt(dh)
+        s = np.where(np.tril(np.ones((seq, seq), bool)), s, -np.inf)
+        mx = s.max(axis=1)
+        ref = mx + np.log(np.exp(s - mx[:, None]).sum(axis=1))
+        assert np.max(np.abs(got[0, h] - ref)) < 2e-3 * max(1.0, np.max(np.abs(ref)))
+
+
 def _stage_inputs(shape):
     params = si.stage_params(shape)
     xs = [si.stage_input(shape, m) for m in range(shape.n_microbatches)]
