@@ -216,7 +216,9 @@ def test_softmax_fwd_and_p1(dtype, n_mat, seq, causal):
                                                 (200, 1, 2, 64, False), (1024, 1, 4, 128, True), (8, 1, 1, 64, True),
                                                 # 8 (sequence, head) pairs: the dq product's XCD-grouped tile map;
                                                 # 256 pairs x 3 query tiles: its paired-tile kernel, middle tile alone
-                                                (256, 2, 4, 64, True), (384, 4, 64, 64, True)])
+                                                (256, 2, 4, 64, True), (384, 4, 64, 64, True),
+                                                # 32 pairs x 8 key blocks: several rounds of workgroups per XCD
+                                                (1024, 1, 32, 64, True)])
 def test_fused_attention_backward(seq, nb, H, dh, causal):
     """dq, dk, dv of the fused backward (probabilities rebuilt from the row log-sum-exp) against the oracle's."""
     _say(f"attention p1 seq={seq} batch={nb} heads={H} dh={dh} causal={causal}")
