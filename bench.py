@@ -56,6 +56,7 @@ def main() -> int:
                          "or separate products with the probabilities stashed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-rates", action="store_true")
+    ap.add_argument("--no-graph-replay", action="store_true")
     ap.add_argument("--no-loop-compare", action="store_true",
                     help="skip the extra loop-mode p2 steps (profiles: every dW launch is then a K-concatenated one)")
     ap.add_argument("--no-call-orders", action="store_true",
@@ -194,6 +195,8 @@ def main() -> int:
             t = json.load(fh).get(shape.name)
         if t:
             out["roofline"]["traffic"] = t["hbm_bytes_per_launch"]
+    if not args.no_graph_replay:
+        out["graph_replay"] = graph_replay(st, tbp, torch, xs, dys, x_out, dx_out, M, max(2, min(args.steps, 3)))
     if not args.no_call_orders:
         out["call_orders"] = call_orders(st, tbp, torch, xs, dys, x_out, dx_out, M, statistics.median(p1_ms))
     if not args.no_kernel_rates:
@@ -255,9 +258,11 @@ def other_workload(shape, tbp, torch, dev, steps=3) -> dict:
         if it:
             fwd.append(e[0].elapsed_time(e[1]) / M); p1.append(e[1].elapsed_time(e[2]) / M); p2.append(e[2].elapsed_time(e[3]))
     sizes = st.sizes
+    replayed = graph_replay(st, tbp, torch, [x] * M, [dy] * M, x_out, dx_out, M, steps)
     st.close()
     p2m = statistics.median(p2)
-    return {"p2_tflops": round(p2_flops(shape) / (p2m * 1e-3) / 1e12, 2), "p2_ms": round(p2m, 3),
+    return {"graph_replay": replayed,
+            "p2_tflops": round(p2_flops(shape) / (p2m * 1e-3) / 1e12, 2), "p2_ms": round(p2m, 3),
             "p1_ms_per_microbatch": round(statistics.median(p1), 3), "fwd_ms_per_microbatch": round(statistics.median(fwd), 3),
             "dtype": shape.dtype, "tokens_per_microbatch": shape.tokens, "n_microbatches": M,
             "stash_bytes": sizes["w_stash_bytes"] + sizes["a_stash_bytes"]}
@@ -355,6 +360,38 @@ def call_orders(st, tbp, torch, xs, dys, x_out, dx_out, M, p1_deferred_ms) -> di
         if k < M:
             run(f"flush_every_{k}", flush_every(k))
     return res
+
+
+def graph_replay(st, tbp, torch, xs, dys, x_out, dx_out, M, reps) -> dict:
+    """The three phases of a step recorded once into HIP graphs (the library allocates and synchronises nothing, so
+    its launches are captured as they are) and replayed: what the host-side launch path costs next to the eager
+    calls that the headline figures time.  Outside the timed steps."""
+    import statistics
+    graphs = [torch.cuda.CUDAGraph() for _ in range(3)]
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graphs[0]):
+        for m in range(M):
+            st.forward(m, xs[m], x_out)
+    with torch.cuda.graph(graphs[1]):
+        for m in range(M):
+            st.backward_p1(m, dys[m], dx_out)
+    with torch.cuda.graph(graphs[2]):
+        st.backward_p2(range(M), tbp.TBP_P2_KCONCAT, accumulate=False)
+    ms = [[], [], []]
+    for r in range(reps + 1):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for i in range(3):
+            e[i].record()
+            graphs[i].replay()
+        e[3].record()
+        torch.cuda.synchronize()
+        if r:                                  # the first replay warms up
+            for i in range(3):
+                ms[i].append(e[i].elapsed_time(e[i + 1]))
+    del graphs
+    return {"fwd_ms_per_microbatch": round(statistics.median(ms[0]) / M, 3),
+            "p1_ms_per_microbatch": round(statistics.median(ms[1]) / M, 3),
+            "p2_ms": round(statistics.median(ms[2]), 3)}
 
 
 def kernel_rates(shape, tbp, torch, dev, tdt) -> dict:
