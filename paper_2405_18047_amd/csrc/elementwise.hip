@@ -258,20 +258,31 @@ __global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float 
 }
 
 // out[col] (= or +=) sum_r parts[row_r][col]; rows given by value (host list) or the first n_first_rows rows.
-// A workgroup covers 32 columns with 8 row lanes each (128-byte coalesced reads, 8 partial sums folded in LDS in
-// a fixed order, so the result is reproducible).
+// A workgroup covers kColsumCols columns with 16 row lanes each (64-byte reads of rows that sit in the L2, which the
+// producing kernel has just written; 16 partial sums folded in LDS in a fixed order, so the result is reproducible).
+constexpr int kColsumCols = 16;
 struct RowList { int n; int idx[64]; };
 __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ parts, RowList rl, int n_first_rows,
                                                      int d, int accumulate, float* __restrict__ out) {
-  __shared__ float fold[8][33];
-  const int c = threadIdx.x & 31, rlane = threadIdx.x >> 5;
-  const int col = blockIdx.x * 32 + c;
+  __shared__ float fold[16][kColsumCols + 1];
+  const int c = threadIdx.x & (kColsumCols - 1), rlane = threadIdx.x / kColsumCols;
+  const int col = blockIdx.x * kColsumCols + c;
   float s = 0.f;
   if (col < d) {
     if (n_first_rows > 0) {
-      for (int r = rlane; r < n_first_rows; r += 8) s += parts[(long)r * d + col];
+      // four independent chains per lane (rows r, r + 16, r + 32, r + 48 of each group of 64): the loads of a group
+      // are in flight together instead of one after the other; the chains are added in a fixed order
+      float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+      int r = rlane;
+      for (; r + 48 < n_first_rows; r += 64) {
+        const float v0 = parts[(long)r * d + col], v1 = parts[(long)(r + 16) * d + col];
+        const float v2 = parts[(long)(r + 32) * d + col], v3 = parts[(long)(r + 48) * d + col];
+        a0 += v0; a1 += v1; a2 += v2; a3 += v3;
+      }
+      for (; r < n_first_rows; r += 16) a0 += parts[(long)r * d + col];
+      s = (a0 + a1) + (a2 + a3);
     } else {
-      for (int r = rlane; r < rl.n; r += 8) s += parts[(long)rl.idx[r] * d + col];
+      for (int r = rlane; r < rl.n; r += 16) s += parts[(long)rl.idx[r] * d + col];
     }
   }
   fold[rlane][c] = s;
@@ -279,7 +290,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ p
   if (rlane == 0 && col < d) {
     float t = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; i++) t += fold[i][c];
+    for (int i = 0; i < 16; i++) t += fold[i][c];
     out[col] = accumulate ? out[col] + t : t;
   }
 }
@@ -613,7 +624,7 @@ static hipError_t rmsnorm_p1_t(int rows, int d, float eps, const void* dy, const
   else e = rmsnorm_p1_w<T, 8, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, parts, &nblk, s);
   if (e != hipSuccess || !dg_out) return e;
   RowList rl{};
-  hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, (const float*)partials, rl, nblk, d,
+  hipLaunchKernelGGL(colsum_kernel, dim3((d + kColsumCols - 1) / kColsumCols), dim3(256), 0, s, (const float*)partials, rl, nblk, d,
                      accumulate, dg_out);
   return hipGetLastError();
 }
@@ -622,7 +633,7 @@ hipError_t rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, con
   if (rows <= 0) {      // no rows: the gain gradient is zero (written by the same column-sum kernel)
     if (!dg_out) return hipSuccess;
     RowList none{};
-    hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, (const float*)partials, none, 0, d, 0,
+    hipLaunchKernelGGL(colsum_kernel, dim3((d + kColsumCols - 1) / kColsumCols), dim3(256), 0, s, (const float*)partials, none, 0, d, 0,
                        dg_out);
     return hipGetLastError();
   }
@@ -635,7 +646,7 @@ hipError_t rmsnorm_gain_p2(int dtype, int rows, int d, float eps, const void* dy
   if (rows <= 0) {
     if (accumulate) return hipSuccess;
     RowList none{};
-    hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, (const float*)partials, none, 0, d, 0,
+    hipLaunchKernelGGL(colsum_kernel, dim3((d + kColsumCols - 1) / kColsumCols), dim3(256), 0, s, (const float*)partials, none, 0, d, 0,
                        dg_out);
     return hipGetLastError();
   }
@@ -650,7 +661,7 @@ hipError_t gain_grad_sum(const float* parts, const int* rows_host, int n, int d,
     RowList rl{};
     rl.n = (n - done) < 64 ? (n - done) : 64;
     for (int i = 0; i < rl.n; i++) rl.idx[i] = rows_host[done + i];
-    hipLaunchKernelGGL(colsum_kernel, dim3((d + 31) / 32), dim3(256), 0, s, parts, rl, 0, d,
+    hipLaunchKernelGGL(colsum_kernel, dim3((d + kColsumCols - 1) / kColsumCols), dim3(256), 0, s, parts, rl, 0, d,
                        (accumulate || done > 0) ? 1 : 0, out);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
