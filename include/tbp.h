@@ -17,6 +17,12 @@
  *   - All device work is enqueued on the hipStream_t passed as `void* stream` (NULL = the null
  *     stream) and the call returns without synchronising.  Device-side failures detectable at
  *     launch time are reported as TBP_EDEVICE.
+ *   - What a call enqueues is kernels and device-to-device copies only (no allocation, no memset, no
+ *     synchronisation, no host callback), and nothing on the device depends on an earlier call except
+ *     through the buffers themselves: the calls can be recorded into a HIP graph with stream capture
+ *     and replayed.  A stage's per-micro-batch state advances when a call is recorded, not when the
+ *     graph runs, so record sequences that a replay may repeat as they are (a whole step returns every
+ *     micro-batch to EMPTY).
  *   - Argument errors are detected on the host before anything is launched (TBP_EINVAL /
  *     TBP_ESTATE / TBP_ENOMEM): a failing call launches nothing and changes no state.
  *   - Layouts: activations and gradients are token-major, row-major [tokens, width] with

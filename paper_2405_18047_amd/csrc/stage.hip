@@ -201,8 +201,7 @@ struct tbp_stage {
   std::vector<int> state;       // per micro-batch
   std::vector<int> slot_of;     // per micro-batch, -1 if none
   std::vector<int> free_slots;
-  bool rope_ready;
-  bool split_ready;             // the arrival counters of the split products have been cleared once
+  std::vector<tbp::GroupedProduct> grouped;      // loop-mode p2: the products of one micro-batch (capacity fixed at creation)
   size_t w_live, a_live, high;
 
   void* wslab(int layer, int t, int mb) const {
@@ -243,8 +242,9 @@ hipError_t linear_gemm(tbp_stage* st, GemmArgs g, hipStream_t s) {
     if (plan.split > 1 && plan.bytes <= st->y.ws_split_bytes) {
       g.ws = st->ws(st->y.ws_split);
       g.ws_bytes = st->y.ws_split_bytes;
-      g.ws_counters_zero = st->split_ready ? 1 : 0;
-      st->split_ready = true;
+      // The arrival counters are cleared before every such product (one small launch) rather than once: a flag kept on
+      // the host would be wrong for a caller who records the first call into a graph and replays it later.
+      g.ws_counters_zero = 0;
     }
   }
   return tbp::gemm(c.dtype, g, s);
@@ -254,10 +254,11 @@ tbp_status run_forward(tbp_stage* st, int mb, int slot, const void* x_in, void* 
   const Dims& c = st->c;
   const int dt = c.dtype, T = c.T, d = c.d, f = c.f;
   const size_t act_bytes = (size_t)T * d * c.e;
-  if (c.attn && !st->rope_ready) {
-    TBP_HIP(tbp::rope_table(c.S, c.dh, c.base, (float2*)st->ws(st->y.ws_rope), s));
-    st->rope_ready = true;
-  }
+  // The rotation table is rebuilt by every forward call (a few microseconds) instead of once behind a host-side flag:
+  // the flag would be wrong for a caller who records the first call into a graph and replays it later, and for one who
+  // moves to another stream without synchronising.  (Every build writes the same values, so a backward-p1 call that
+  // reads the table on another stream meanwhile reads them either way.)
+  if (c.attn) TBP_HIP(tbp::rope_table(c.S, c.dh, c.base, (float2*)st->ws(st->y.ws_rope), s));
   const void* x_cur = x_in;
   for (int l = 0; l < c.L; l++) {
     void* x1 = st->x1_of(l, mb, slot);
@@ -438,7 +439,7 @@ tbp_status run_p2(tbp_stage* st, const int* mbs, int n, int mode, int accumulate
     // bf16, one micro-batch per product: all weight-gradient products of the stage for that micro-batch go into one
     // grouped launch, each launch accumulating on the previous one.  (The K-concatenated products are long enough
     // that one launch per weight, which starts its tiles in step, is the faster arrangement.)
-    std::vector<tbp::GroupedProduct> table;
+    std::vector<tbp::GroupedProduct>& table = st->grouped;     // (no host allocation here: the capacity is reserved)
     for (int i = 0; i < n; i++) {
       table.clear();
       const int mb0 = mbs[i];
@@ -541,22 +542,28 @@ tbp_status tbp_stage_create(const tbp_config* cfg, const tbp_params* params, voi
   tbp_stage* st = new (std::nothrow) tbp_stage();
   if (!st) return fail(TBP_ENOMEM, "host allocation failed");
   st->c = c; st->y = y; st->arena = static_cast<unsigned char*>(arena);
-  bool ok = copy_ptrs(st->w_gu, params->w_gu, c.L) && copy_ptrs(st->w_d, params->w_d, c.L) &&
-            copy_ptrs(st->g2, params->g2, c.L) && copy_ptrs(st->dw_gu, params->dw_gu, c.L) &&
-            copy_ptrs(st->dw_d, params->dw_d, c.L) && copy_ptrs(st->dg2, params->dg2, c.L);
-  if (ok && c.attn)
-    ok = copy_ptrs(st->w_qkv, params->w_qkv, c.L) && copy_ptrs(st->w_o, params->w_o, c.L) &&
-         copy_ptrs(st->g1, params->g1, c.L) && copy_ptrs(st->dw_qkv, params->dw_qkv, c.L) &&
-         copy_ptrs(st->dw_o, params->dw_o, c.L) && copy_ptrs(st->dg1, params->dg1, c.L);
+  bool ok = false;
+  try {                                        // (no exception may leave through the C boundary)
+    ok = copy_ptrs(st->w_gu, params->w_gu, c.L) && copy_ptrs(st->w_d, params->w_d, c.L) &&
+         copy_ptrs(st->g2, params->g2, c.L) && copy_ptrs(st->dw_gu, params->dw_gu, c.L) &&
+         copy_ptrs(st->dw_d, params->dw_d, c.L) && copy_ptrs(st->dg2, params->dg2, c.L);
+    if (ok && c.attn)
+      ok = copy_ptrs(st->w_qkv, params->w_qkv, c.L) && copy_ptrs(st->w_o, params->w_o, c.L) &&
+           copy_ptrs(st->g1, params->g1, c.L) && copy_ptrs(st->dw_qkv, params->dw_qkv, c.L) &&
+           copy_ptrs(st->dw_o, params->dw_o, c.L) && copy_ptrs(st->dg1, params->dg1, c.L);
+    st->state.assign(c.Mmax, MB_EMPTY);
+    st->slot_of.assign(c.Mmax, -1);
+    st->free_slots.reserve(c.slots);
+    for (int i = c.slots - 1; i >= 0; i--) st->free_slots.push_back(i);
+    st->grouped.reserve((size_t)4 * c.L);
+  } catch (...) {
+    delete st;
+    return fail(TBP_ENOMEM, "host allocation failed");
+  }
   if (!ok) {
     delete st;
     return fail(TBP_EINVAL, "a parameter or gradient pointer (array or entry) is null");
   }
-  st->state.assign(c.Mmax, MB_EMPTY);
-  st->slot_of.assign(c.Mmax, -1);
-  for (int i = c.slots - 1; i >= 0; i--) st->free_slots.push_back(i);
-  st->rope_ready = false;
-  st->split_ready = false;
   st->w_live = st->a_live = st->high = 0;
   *out = st;
   return TBP_OK;

@@ -73,3 +73,58 @@ def test_step_replayed_from_a_graph_equals_the_eager_step(mode):
         step()
         torch.cuda.synchronize()
     st.close()
+
+
+@pytest.mark.parametrize("shape", [
+    si.StageShape("graph_first_bf16", 1, 512, 4, 128, 1032, 264, 1, 2, "bf16", 37),       # attention: rotation table
+    si.StageShape("graph_first_long_k", 1, 1024, 0, 0, 24576, 1024, 1, 2, "bf16", 38),    # a product with a split contraction
+], ids=lambda s: s.name)
+def test_graph_recorded_before_any_eager_call(shape):
+    """A stage whose very first calls are recorded, not run: nothing the later eager calls rely on (rotation table,
+    cleared counters) may have been set up by a launch that so far exists only in the graph."""
+    print(f"graph recorded before any eager call, shape={shape}", flush=True)
+    params = si.stage_params(shape)
+    n = shape.n_microbatches
+    xs = [to_dev(si.stage_input(shape, m), shape.dtype) for m in range(n)]
+    dys = [to_dev(si.stage_upstream_grad(shape, m), shape.dtype) for m in range(n)]
+    x_out = [torch.empty_like(t) for t in xs]
+    dx_out = [torch.empty_like(t) for t in xs]
+    st = make_gpu_stage(shape, params)
+
+    def step():
+        for m in range(n):
+            st.forward(m, xs[m], out=x_out[m])
+        for m in range(n):
+            st.backward_p1(m, dys[m], out=dx_out[m])
+        st.backward_p2(range(n), tbp.TBP_P2_KCONCAT, accumulate=False)
+
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    step()                                     # eager, before the graph has ever run
+    torch.cuda.synchronize()
+    want = ([t.clone() for t in x_out], [t.clone() for t in dx_out], {k: [g.clone() for g in v] for k, v in st.grads.items()})
+    for t in x_out + dx_out:
+        t.zero_()
+    st.zero_grads()
+    graph.replay()
+    torch.cuda.synchronize()
+    for m in range(n):
+        assert torch.equal(x_out[m], want[0][m]) and torch.equal(dx_out[m], want[1][m]), m
+    for k, v in st.grads.items():
+        for l, g in enumerate(v):
+            assert torch.equal(g, want[2][k][l]), (k, l)
+    # and the eager result is the right one: compare with a second stage that never saw a graph
+    ref = make_gpu_stage(shape, params)
+    outs = [ref.forward(m, xs[m]) for m in range(n)]
+    dxs = [ref.backward_p1(m, dys[m]) for m in range(n)]
+    ref.backward_p2(range(n), tbp.TBP_P2_KCONCAT, accumulate=False)
+    torch.cuda.synchronize()
+    for m in range(n):
+        assert torch.equal(outs[m], want[0][m]) and torch.equal(dxs[m], want[1][m]), m
+    for k, v in ref.grads.items():
+        for l, g in enumerate(v):
+            assert torch.equal(g, want[2][k][l]), (k, l)
+    ref.close()
+    st.close()
