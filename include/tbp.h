@@ -173,7 +173,8 @@ tbp_status tbp_stage_reset(tbp_stage* st);
  * out_f32 != 0: C is fp32 (and may accumulate); else C has the storage type and R (optional,
  * same shape and leading dimension as C) is added before rounding.
  * bf16 storage: A, B, C and R must be 16-byte aligned; the contiguous extent of A and of B, N, lda, ldb and
- * ldc must be multiples of 8 (every lane moves 16 bytes); TBP_EINVAL otherwise.  fp32 storage has no such rule.
+ * ldc must be multiples of 8 (every lane moves 16 bytes) and lda, ldb below 2^22 elements; TBP_EINVAL otherwise.
+ * fp32 storage has no such rule.
  * K == 0 writes zeros (or leaves an accumulated C alone); M == 0 or N == 0 does nothing. */
 tbp_status tbp_gemm(int dtype, int layout, int M, int N, int K, float alpha, const void* A, int lda,
                     const void* B, int ldb, void* C, int ldc, int out_f32, int accumulate, const void* R,
@@ -220,7 +221,8 @@ tbp_status tbp_softmax_p1(int dtype, int n_mat, int seq, int causal, const void*
  * q | k | v of n_heads*head_dim each (q and k already rotated); out: device [batch*seq, ld_out], heads concatenated;
  * lse: device [batch, n_heads, seq] fp32 = log2 of the row's sum of exp2(score * log2(e) / sqrt(head_dim)), all that
  * backward-p1 needs to rebuild the probabilities.  causal != 0: query i sees keys j <= i.  Pointers 16-byte aligned,
- * leading dimensions multiples of 8.  Neither scores nor probabilities are written to memory. */
+ * leading dimensions multiples of 8, seq * ld_qkv * 2 below 2^32 (one sequence's rows span less than 4 GiB).  Neither
+ * scores nor probabilities are written to memory. */
 tbp_status tbp_attention_fwd(int dtype, int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv,
                              int ld_qkv, void* out, int ld_out, float* lse, void* stream);
 

@@ -677,6 +677,8 @@ tbp_status tbp_gemm_ws(int dtype, int layout, int M, int N, int K, float alpha, 
     if ((uintptr_t)A % 16 || (uintptr_t)B % 16 || (uintptr_t)C % 16 || (R && (uintptr_t)R % 16))
       return fail(TBP_EINVAL, "bf16-path operands, output and residual must be 16-byte aligned");
     if (N % 8 || ldc % 8) return fail(TBP_EINVAL, "bf16 path needs N and ldc to be multiples of 8");
+    // (a tile's 256 rows are addressed through a 31-bit buffer range)
+    if (lda >= (1 << 22) || ldb >= (1 << 22)) return fail(TBP_EINVAL, "bf16 path needs leading dimensions below 2^22 elements");
   }
   if (dtype == TBP_F32) out_f32 = 1;
   if (accumulate && !out_f32) return fail(TBP_EINVAL, "accumulate needs an fp32 output");
@@ -701,6 +703,8 @@ tbp_status tbp_attention_fwd(int dtype, int batch, int n_heads, int seq, int hea
   if (ld_qkv < 3 * n_heads * head_dim || ld_out < n_heads * head_dim || ld_qkv % 8 || ld_out % 8)
     return fail(TBP_EINVAL, "leading dimensions must cover the head columns and be multiples of 8");
   if ((uintptr_t)qkv % 16 || (uintptr_t)out % 16) return fail(TBP_EINVAL, "qkv and out must be 16-byte aligned");
+  // (the kernels address one sequence's rows through a 32-bit buffer range)
+  if ((long)seq * ld_qkv * 2 >= (1L << 32)) return fail(TBP_EINVAL, "seq * ld_qkv too large: a sequence's rows must span less than 4 GiB");
   if (seq % 8) return fail(TBP_EINVAL, "seq must be a multiple of 8");
   if (seq > tbp::kMaxSeq) return fail(TBP_EINVAL, "seq %d above the limit %d", seq, tbp::kMaxSeq);
   TBP_HIP(tbp::attention_fwd(batch, n_heads, seq, head_dim, causal ? 1 : 0, qkv, ld_qkv, out, ld_out, lse,
@@ -724,6 +728,8 @@ tbp_status tbp_attention_p1(int dtype, int batch, int n_heads, int seq, int head
   const int d = n_heads * head_dim;
   if (ld_qkv < 3 * d || ld_dqkv < 3 * d || ld_qkv % 8 || ld_dqkv % 8) return fail(TBP_EINVAL, "leading dimensions must cover 3*n_heads*head_dim and be multiples of 8");
   if (ld_out != d) return fail(TBP_EINVAL, "out and d_out must be dense [batch*seq, n_heads*head_dim]");
+  if ((long)seq * ld_qkv * 2 >= (1L << 32) || (long)seq * ld_dqkv * 2 >= (1L << 32))
+    return fail(TBP_EINVAL, "seq * leading dimension too large: a sequence's rows must span less than 4 GiB");
   if (seq % 8) return fail(TBP_EINVAL, "seq must be a multiple of 8");
   if (seq > tbp::kMaxSeq) return fail(TBP_EINVAL, "seq %d above the limit %d", seq, tbp::kMaxSeq);
   if ((uintptr_t)qkv % 16 || (uintptr_t)out % 16 || (uintptr_t)d_out % 16 || (uintptr_t)dqkv % 16 || (uintptr_t)scratch % 256)

@@ -150,6 +150,11 @@ def test_single_op_argument_checks():
     assert L.tbp_softmax_fwd(1, 1, 8192, 1, fake, fake, None) == 1
     assert L.tbp_rope(1, 4, 8, 2, 24, 48, fake, 0, fake, None) == 1
     assert L.tbp_rmsnorm_p1_scratch_bytes(4096) == 256 * 4096 * 4
+    # leading dimensions beyond what the kernels' buffer ranges address are refused, not wrapped
+    assert L.tbp_gemm(1, 0, 64, 64, 64, 1.0, fake, 1 << 22, fake, 64, fake, 64, 0, 0, None, None) == 1
+    assert L.tbp_attention_fwd(1, 1, 2, 4096, 64, 1, fake, 1 << 19, fake, 128, fake, None) == 1
+    # dS^T scratch of the fused attention backward: row sums + panels of 128 queries (seq rounded up to 128 on one side)
+    assert L.tbp_attention_p1_scratch_bytes(2, 3, 200) == 4864 + 2 * 3 * 2 * 200 * 128 * 2
 
 
 def test_gemm_workspace_policy_and_checks():
