@@ -343,18 +343,18 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
     bf16x8 kfb[KS], vfb[KS];
     const long ds_elems = (long)attn_ds_elems(p.S);
     const u32x4 rst = make_desc(p.dst + bh * ds_elems, (uint32_t)(ds_elems * 2));
-    // The tile of dS^T (32 keys x 32 queries) leaves through a per-wave LDS buffer (rows padded to 80 bytes against bank
-    // conflicts): a lane holds 4 consecutive queries of its key row per register group, which stored directly is 8 bytes
-    // per lane and 32 rows per instruction; read back row-major it is 16 bytes per lane, 64 contiguous bytes per key row
-    // and 16 rows per instruction.
-    constexpr int STG_ROW = 80;
+    // The tiles of dS^T (32 keys x 32 queries each) leave through a per-wave LDS buffer that collects the two tiles of a
+    // 64-query step (rows padded to 144 bytes against bank conflicts): a lane holds 4 consecutive queries of its key row
+    // per register group, which stored directly is 8 bytes per lane and 32 rows per instruction; read back row-major
+    // after the second tile it is 16 bytes per lane and 128 contiguous bytes (a whole cache line of the panel) per key row.
+    constexpr int STG_ROW = 144;
     lds_u8* const stg = hand + 2 * HAND + wave * (32 * STG_ROW);
-    lds_u8* const stg_wr = stg + kl * STG_ROW + 8 * g;          // + 16 e4
-    unsigned st_row[2];
+    lds_u8* const stg_wr = stg + kl * STG_ROW + 8 * g;          // + 64 (tile & 1) + 16 e4
+    unsigned st_row[4];
 #pragma unroll
-    for (int r = 0; r < 2; r++) {
-      const int row = (lane + 64 * r) >> 2;
-      st_row[r] = kw0 + row < p.S ? (unsigned)(((kw0 + row) * kPanel + 8 * (lane & 3)) * 2) : kOob;
+    for (int r = 0; r < 4; r++) {
+      const int row = (lane + 64 * r) >> 3;
+      st_row[r] = kw0 + row < p.S ? (unsigned)(((kw0 + row) * kPanel + 8 * (lane & 7)) * 2) : kOob;
     }
     __syncthreads();                                          // steps step0, step0 + 1 and the K / V rows have landed
     // the lane's key row and value row as B operands (8 consecutive head-dim values per k-step), from the images the
@@ -417,15 +417,17 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
         const u32x4 s0 = __builtin_bit_cast(u32x4, ks[0]), s1 = __builtin_bit_cast(u32x4, ks[1]);
         const u32x2 dsv[4] = {u32x2{s0[0], s0[1]}, u32x2{s0[2], s0[3]}, u32x2{s1[0], s1[1]}, u32x2{s1[2], s1[3]}};
 #pragma unroll
-        for (int e4 = 0; e4 < 4; e4++) *reinterpret_cast<LDS_AS u32x2*>(stg_wr + 16 * e4) = dsv[e4];
-        // (LDS operations of a wave execute in order: the reads below see the writes above)
+        for (int e4 = 0; e4 < 4; e4++) *reinterpret_cast<LDS_AS u32x2*>(stg_wr + 64 * (tile & 1) + 16 * e4) = dsv[e4];
+        // (LDS operations of a wave execute in order: the reads below see the writes above and those of the tile before)
+        if (tile & 1) {
+          const int qe = qt0 - 32;                              // first query of the step; the step lies inside one panel
+          const long pan = ((long)(qe / kPanel) * p.S * kPanel + qe % kPanel) * 2;
 #pragma unroll
-        for (int r = 0; r < 2; r++) {
-          const int idx = lane + 64 * r;
-          const u32x4 v = *reinterpret_cast<const LDS_AS u32x4*>(stg + (idx >> 2) * STG_ROW + 16 * (idx & 3));
-          // panel qt0 / 128 starts at (qt0 / 128) * S * 128 elements; the tile's queries are columns qt0 % 128 .. + 31 of it
-          const long pan = ((long)(qt0 / kPanel) * p.S * kPanel + qt0 % kPanel) * 2;
-          store16_async(v, rst, qt0 + 8 * (lane & 3) < p.S ? st_row[r] : kOob, (uint32_t)__builtin_amdgcn_readfirstlane((int)pan));
+          for (int r = 0; r < 4; r++) {
+            const int idx = lane + 64 * r;
+            const u32x4 v = *reinterpret_cast<const LDS_AS u32x4*>(stg + (idx >> 3) * STG_ROW + 16 * (idx & 7));
+            store16_async(v, rst, qe + 8 * (lane & 7) < p.S ? st_row[r] : kOob, (uint32_t)__builtin_amdgcn_readfirstlane((int)pan));
+          }
         }
       }
       __syncthreads();
@@ -605,7 +607,7 @@ hipError_t attention_fwd(int batch, int n_heads, int seq, int head_dim, int caus
 
 template <int DH>
 static hipError_t launch_bwd_kv_split(const AttnBwdParams& p, hipStream_t s) {
-  constexpr size_t smem = 3 * (2 * 64 * DH * 2 + 1024) + 2 * 4 * 4096 + 4 * 32 * 80;     // three slots, two hand-over buffers, dS^T staging
+  constexpr size_t smem = 3 * (2 * 64 * DH * 2 + 1024) + 2 * 4 * 4096 + 4 * 32 * 144;     // three slots, two hand-over buffers, dS^T staging
   auto kern = attn_bwd_kv_split_kernel<DH>;
   static bool attr_set = false;
   if (!attr_set) {
