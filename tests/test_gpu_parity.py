@@ -218,7 +218,9 @@ def test_softmax_fwd_and_p1(dtype, n_mat, seq, causal):
                                                 # 256 pairs x 3 query tiles: its paired-tile kernel, middle tile alone
                                                 (256, 2, 4, 64, True), (384, 4, 64, 64, True),
                                                 # 32 pairs x 8 key blocks: several rounds of workgroups per XCD
-                                                (1024, 1, 32, 64, True)])
+                                                (1024, 1, 32, 64, True),
+                                                # the longest sequence the kernels take
+                                                (4096, 1, 1, 128, True)])
 def test_fused_attention_backward(seq, nb, H, dh, causal):
     """dq, dk, dv of the fused backward (probabilities rebuilt from the row log-sum-exp) against the oracle's."""
     _say(f"attention p1 seq={seq} batch={nb} heads={H} dh={dh} causal={causal}")
@@ -238,7 +240,8 @@ def test_fused_attention_backward(seq, nb, H, dh, causal):
 
 # ------------------------------------------------------------------------------------------- whole stage
 @pytest.mark.parametrize("seq,nb,H,dh,causal", [(256, 1, 2, 128, True), (136, 2, 3, 64, True), (520, 1, 2, 128, True),
-                                                (200, 1, 2, 64, False), (1024, 1, 4, 128, True), (8, 1, 1, 64, True)])
+                                                (200, 1, 2, 64, False), (1024, 1, 4, 128, True), (8, 1, 1, 64, True),
+                                                (4096, 1, 1, 128, True)])
 def test_fused_attention_forward(seq, nb, H, dh, causal):
     """Fused attention against the oracle's materialised form; the row log-sum-exp against what the oracle's
     probabilities imply (lse_i = s_ii - log P_ii on the diagonal, which is never masked)."""
