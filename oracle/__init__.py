@@ -25,6 +25,7 @@ from .ops import (  # noqa: F401
     rmsnorm_fwd, rmsnorm_p1, rmsnorm_p2,
     swiglu_fwd, swiglu_p1,
     rope_fwd, rope_p1,
+    softmax_fwd, softmax_p1,
     attention_fwd, attention_p1,
 )
 from .stage import OracleStage  # noqa: F401

@@ -107,6 +107,24 @@ def rope_p1(dy, seq, n_heads, head_dim, base):
 
 
 # ----------------------------------------------------------------------------------------------
+# Row softmax with an optional causal mask, and its backward-p1 (Section 3.2 names the softmax
+# backward-p1 as one of the operations worth compiling).  Functional: no backward-p2.
+# ----------------------------------------------------------------------------------------------
+def softmax_fwd(s, causal=False):
+    """P = softmax over the last axis of s [..., S, S]; causal: entry (i, j) with j > i is masked (P = 0 exactly)."""
+    if causal:
+        n = s.shape[-1]
+        s = np.where(np.triu(np.ones((n, n), dtype=bool), k=1), -np.inf, s)
+    e = np.exp(s - np.max(s, axis=-1, keepdims=True))
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def softmax_p1(p, dp):
+    """dL/dS from dL/dP and the forward's P:  dS = P * (dP - rowsum(dP * P)).  Masked entries have P = 0, so dS = 0."""
+    return p * (dp - np.sum(dp * p, axis=-1, keepdims=True))
+
+
+# ----------------------------------------------------------------------------------------------
 # Scaled dot-product attention per (sequence, head), scores scaled by 1/sqrt(dh), optional causal
 # mask (query i sees keys j <= i).  A functional module: backward-p1 only (Section 4.1).
 # ----------------------------------------------------------------------------------------------
@@ -117,17 +135,12 @@ def attention_fwd(q, k, v, seq, n_heads, head_dim, causal=True):
     scale = 1.0 / np.sqrt(float(head_dim))
     o = np.empty_like(q)
     p_all = np.zeros((nb, n_heads, seq, seq), dtype=q.dtype)
-    mask = np.triu(np.ones((seq, seq), dtype=bool), k=1) if causal else None
     for b in range(nb):
         rows = slice(b * seq, (b + 1) * seq)
         for h in range(n_heads):
             cols = slice(h * head_dim, (h + 1) * head_dim)
             s = (q[rows, cols] @ k[rows, cols].T) * q.dtype.type(scale)
-            if causal:
-                s = np.where(mask, -np.inf, s)
-            s = s - np.max(s, axis=-1, keepdims=True)
-            e = np.exp(s)
-            p = e / np.sum(e, axis=-1, keepdims=True)
+            p = softmax_fwd(s, causal)
             p_all[b, h] = p
             o[rows, cols] = p @ v[rows, cols]
     return o, p_all
@@ -136,7 +149,7 @@ def attention_fwd(q, k, v, seq, n_heads, head_dim, causal=True):
 def attention_p1(do, q, k, v, p_all, seq, n_heads, head_dim):
     """(dq, dk, dv) from the upstream do and the forward's probabilities P.
 
-    dv = P^T do;  dP = do v^T;  dS = P * (dP - rowsum(dP * P));  dq = dS k / sqrt(dh);
+    dv = P^T do;  dP = do v^T;  dS = softmax_p1(P, dP);  dq = dS k / sqrt(dh);
     dk = dS^T q / sqrt(dh).  Masked entries have P = 0 and therefore dS = 0.
     """
     t = q.shape[0]
@@ -150,7 +163,7 @@ def attention_p1(do, q, k, v, p_all, seq, n_heads, head_dim):
             p = p_all[b, h]
             dv[rows, cols] = p.T @ do[rows, cols]
             dp = do[rows, cols] @ v[rows, cols].T
-            ds = p * (dp - np.sum(dp * p, axis=-1, keepdims=True))
+            ds = softmax_p1(p, dp)
             dq[rows, cols] = (ds @ k[rows, cols]) * scale
             dk[rows, cols] = (ds.T @ q[rows, cols]) * scale
     return dq, dk, dv

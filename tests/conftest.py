@@ -8,10 +8,6 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-def pytest_configure(config):
-    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-
-
 @pytest.fixture(scope="session")
 def tiny_shape():
     from seeded_inputs import StageShape

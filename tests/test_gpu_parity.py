@@ -47,7 +47,8 @@ def test_gemm_matches_definition(dtype, layout, mnk):
     b_shape = (N, K) if layout == tbp.NT else (K, N)
     A, B = _rnd(11, "A", a_shape, dtype), _rnd(11, "B", b_shape, dtype)
     a64, b64 = A.astype(np.float64), B.astype(np.float64)
-    ref = (a64.T if layout == tbp.TN else a64) @ (b64.T if layout == tbp.NT else b64)
+    # the three layouts are the three products of a linear layer: forward, backward-p1, backward-p2
+    ref = {tbp.NN: ops.linear_fwd, tbp.NT: ops.linear_p1, tbp.TN: ops.linear_p2}[layout](a64, b64)
     dA, dB = to_dev(A, dtype), to_dev(B, dtype)
     got32 = tbp.tbp_gemm(layout, dA, dB, out_f32=True)
     assert max_rel(to_np(got32), ref) < 2e-5
@@ -83,7 +84,7 @@ def test_gemm_with_split_contraction(layout, mnk):
     A, B = _rnd(13, "A", a_shape, dtype), _rnd(13, "B", b_shape, dtype)
     R = _rnd(13, "R", (M, N), dtype, 4.0)
     a64, b64 = A.astype(np.float64), B.astype(np.float64)
-    ref = a64 @ (b64.T if layout == tbp.NT else b64)
+    ref = ops.linear_p1(a64, b64) if layout == tbp.NT else ops.linear_fwd(a64, b64)
     dA, dB, dR = to_dev(A, dtype), to_dev(B, dtype), to_dev(R, dtype)
     ws = torch.empty(need + 4096, dtype=torch.uint8, device=DEV).fill_(0xA5)      # junk, larger than needed
     got1 = tbp.tbp_gemm(layout, dA, dB, workspace=ws)
@@ -108,9 +109,9 @@ def test_gemm_strided_views_and_empty():
     d_big, d_w = to_dev(big, dtype), to_dev(W, dtype)
     view = d_big[:, 128:256]
     got = tbp.tbp_gemm(tbp.NN, view, d_w, out_f32=True)
-    assert max_rel(to_np(got), big[:, 128:256].astype(np.float64) @ W.astype(np.float64)) < 2e-5
+    assert max_rel(to_np(got), ops.linear_fwd(big[:, 128:256].astype(np.float64), W.astype(np.float64))) < 2e-5
     got = tbp.tbp_gemm(tbp.TN, view, d_big[:, 256:], out_f32=True)
-    assert max_rel(to_np(got), big[:, 128:256].astype(np.float64).T @ big[:, 256:].astype(np.float64)) < 2e-5
+    assert max_rel(to_np(got), ops.linear_p2(big[:, 128:256].astype(np.float64), big[:, 256:].astype(np.float64))) < 2e-5
     # K = 0 gives zeros (or leaves an accumulated C alone); M = 0 is a no-op
     z = tbp.tbp_gemm(tbp.NN, torch.empty((16, 0), dtype=torch.bfloat16, device=DEV),
                      torch.empty((0, 24), dtype=torch.bfloat16, device=DEV), out_f32=True)
@@ -169,15 +170,6 @@ def test_rope_fwd_and_inverse(dtype, seq, nb, H, dh):
         assert np.array_equal(got[:, H * dh:], x64[:, H * dh:])
 
 
-def _softmax_ref(scores, causal):
-    S = scores.shape[-1]
-    s = scores.astype(np.float64)
-    if causal:
-        s = np.where(np.triu(np.ones((S, S), bool), 1), -np.inf, s)
-    e = np.exp(s - s.max(-1, keepdims=True))
-    return e / e.sum(-1, keepdims=True)
-
-
 @pytest.mark.parametrize("dtype,n_mat,seq", [("bf16", 3, 1024), ("bf16", 2, 264), ("bf16", 1, 4096), ("f32", 4, 128),
                                              ("f32", 2, 260)])
 @pytest.mark.parametrize("causal", [True, False])
@@ -186,18 +178,18 @@ def test_softmax_fwd_and_p1(dtype, n_mat, seq, causal):
     sc = _rnd(16, "s", (n_mat, seq, seq), "f32", 3.0)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     P = tbp.tbp_softmax_fwd(to_dev(sc, "f32"), causal, tdt)
-    ref = _softmax_ref(sc, causal)
+    ref = ops.softmax_fwd(sc.astype(np.float64), causal)
     got = to_np(P)
     tol = 4.5e-3 if dtype == "bf16" else 2e-6
     assert max_rel(got, ref) < tol
     if causal:
         iu = np.triu_indices(seq, 1)
         assert np.all(got[:, iu[0], iu[1]] == 0)
-    # backward on the stored probabilities (what the stage does): dS = P * (dP - rowsum(dP * P))
+    # backward on the stored probabilities (what the materialised attention does)
     Pst = si.store_round(ref, dtype)
     dP = _rnd(16, "dp", (n_mat, seq, seq), dtype)
     p64, g64 = Pst.astype(np.float64), dP.astype(np.float64)
-    ds_ref = p64 * (g64 - np.sum(g64 * p64, -1, keepdims=True))
+    ds_ref = ops.softmax_p1(p64, g64)
     ddP = to_dev(dP, dtype)
     if causal:   # the kernel must not depend on what lies above the diagonal: poison it
         ddP = torch.where(torch.triu(torch.ones(seq, seq, dtype=torch.bool, device=DEV), 1), torch.full_like(ddP, float("nan")), ddP)
