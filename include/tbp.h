@@ -197,6 +197,16 @@ tbp_status tbp_rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x,
 tbp_status tbp_rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
                           const void* resid, void* dx, float* dg_out, void* scratch, void* stream);
 size_t tbp_rmsnorm_p1_scratch_bytes(int d);
+/* tbp_rmsnorm_p1 for callers that cannot allocate device memory or carry a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments minus `scratch`, same kernels, same results
+ * bit for bit.  The row-block partials of the gain gradient live in an 8 MiB array inside the library's code object
+ * (256 rows of at most 8192 fp32 columns), resident on every GPU the library is used on until the process ends; its
+ * device address is looked up on the first call on each device (make that first call outside a stream capture).
+ * The call allocates and frees nothing.  d above the limit of the storage type (8192 bf16, 4096 f32) is TBP_EINVAL.
+ * Nothing in the array needs clearing between calls, but every call on a GPU uses that GPU's one array: calls that may
+ * overlap on one GPU (different streams, or threads) race on it and must be ordered by the caller. */
+tbp_status tbp_rmsnorm_p1_static(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
+                                 const void* resid, void* dx, float* dg_out, void* stream);
 /* The gain gradient alone, as a backward-p2 operation (Section 3.1): dg_out [d] fp32 (= or +=) sum over rows of
  * dy * x * rsqrt(mean(x^2) + eps).  dy, x [rows, d] device, storage type; scratch as for tbp_rmsnorm_p1. */
 tbp_status tbp_rmsnorm_gain_p2(int dtype, int rows, int d, float eps, const void* dy, const void* x, int accumulate,

@@ -12,7 +12,7 @@ import torch
 
 __all__ = [
     "TBP_F32", "TBP_BF16", "TBP_P2_LOOP", "TBP_P2_KCONCAT", "TBP_ATTN_AUTO", "TBP_ATTN_MATERIALISED", "TBP_ATTN_FUSED", "TBP_GAIN_PARTIALS", "TBP_GAIN_LITERAL", "NN", "NT", "TN", "TbpError", "lib", "library_path",
-    "tbp_config", "tbp_stash_query", "Stage", "tbp_gemm", "tbp_rmsnorm_fwd", "tbp_rmsnorm_p1", "tbp_rmsnorm_gain_p2", "tbp_swiglu_fwd",
+    "tbp_config", "tbp_stash_query", "Stage", "tbp_gemm", "tbp_rmsnorm_fwd", "tbp_rmsnorm_p1", "tbp_rmsnorm_p1_static", "tbp_rmsnorm_gain_p2", "tbp_swiglu_fwd",
     "tbp_swiglu_p1", "tbp_rope_table", "tbp_rope", "tbp_softmax_fwd", "tbp_softmax_p1", "tbp_version",
     "tbp_attention_fwd", "tbp_attention_p1",
     "config_from_shape",
@@ -80,6 +80,7 @@ def lib() -> C.CDLL:
         L.tbp_gemm_workspace_bytes.restype = C.c_size_t
         L.tbp_rmsnorm_fwd.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float] + [C.c_void_p] * 4
         L.tbp_rmsnorm_p1.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float] + [C.c_void_p] * 8
+        L.tbp_rmsnorm_p1_static.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float] + [C.c_void_p] * 7
         L.tbp_swiglu_fwd.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 3
         L.tbp_swiglu_p1.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 4
         L.tbp_rope_table.argtypes = [C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p]
@@ -274,6 +275,17 @@ def tbp_rmsnorm_p1(dy, x, g, eps, resid=None):
     scratch = torch.empty(lib().tbp_rmsnorm_p1_scratch_bytes(d), dtype=torch.uint8, device=x.device)
     _check(lib().tbp_rmsnorm_p1(_dt(x), rows, d, eps, _ptr(dy), _ptr(x), _ptr(g), _ptr(resid), _ptr(dx), _ptr(dg),
                                 _ptr(scratch), _stream()))
+    return dx, dg
+
+
+def tbp_rmsnorm_p1_static(dy, x, g, eps, resid=None, dx=None, dg=None):
+    """tbp_rmsnorm_p1 without a scratch argument (the library's own static device array).  Pass dx and dg to make the
+    call itself allocation-free."""
+    rows, d = x.shape
+    dx = torch.empty_like(x) if dx is None else dx
+    dg = torch.empty(d, dtype=torch.float32, device=x.device) if dg is None else dg
+    _check(lib().tbp_rmsnorm_p1_static(_dt(x), rows, d, eps, _ptr(dy), _ptr(x), _ptr(g), _ptr(resid), _ptr(dx), _ptr(dg),
+                                       _stream()))
     return dx, dg
 
 

@@ -4,6 +4,7 @@
 #include "kernels.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -764,6 +765,49 @@ tbp_status tbp_rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy,
   if (rows < 0 || d < 1 || d % vecq(dtype) || d > tbp::max_d_model(dtype)) return fail(TBP_EINVAL, "bad rows / d");
   if (!g || !dg_out || !scratch || (rows > 0 && (!dy || !x || !dx))) return fail(TBP_EINVAL, "null pointer");
   TBP_HIP(tbp::rmsnorm_p1(dtype, rows, d, eps, dy, x, g, resid, dx, dg_out, (float*)scratch, static_cast<hipStream_t>(stream)));
+  return TBP_OK;
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------------------------------
+// Scratch of tbp_rmsnorm_p1_static: the row-block partials of the gain gradient, kNormPartialBlocks rows of up to
+// max_d_model(bf16) fp32 columns (8 MiB), resident on every GPU the library runs on until the process ends.  In host
+// code the array's name is only a stand-in for the symbol: its device address is asked for once per device
+// (hipGetSymbolAddress with that device current) and kept in g_static_scratch[device]; only that pointer is ever
+// handed to a kernel.
+constexpr size_t kStaticScratchFloats = (size_t)tbp::kNormPartialBlocks * 8192;
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+constexpr int kMaxDevices = 64;
+static std::atomic<float*> g_static_scratch[kMaxDevices];
+
+static tbp_status static_scratch(float** out) {
+  int dev = -1;
+  TBP_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(TBP_EDEVICE, "device index %d outside 0..%d", dev, kMaxDevices - 1);
+  float* p = g_static_scratch[dev].load(std::memory_order_acquire);
+  if (!p) {           // first call on this device (two threads racing here both obtain the same address)
+    void* sym = nullptr;
+    TBP_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+    if (!sym) return fail(TBP_EDEVICE, "hipGetSymbolAddress returned a null address for the static scratch");
+    p = static_cast<float*>(sym);
+    g_static_scratch[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return TBP_OK;
+}
+
+tbp_status tbp_rmsnorm_p1_static(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
+                                 const void* resid, void* dx, float* dg_out, void* stream) {
+  if (check_dtype(dtype) != TBP_OK) return TBP_EINVAL;
+  if (rows < 0 || d < 1 || d % vecq(dtype)) return fail(TBP_EINVAL, "bad rows / d");
+  if (d > tbp::max_d_model(dtype) || (size_t)tbp::kNormPartialBlocks * d > kStaticScratchFloats)
+    return fail(TBP_EINVAL, "d = %d is above the %d columns (%s) the static scratch of %zu bytes is built for", d,
+                tbp::max_d_model(dtype), dtype == TBP_BF16 ? "bf16" : "f32", kStaticScratchFloats * sizeof(float));
+  if (!g || !dg_out || (rows > 0 && (!dy || !x || !dx))) return fail(TBP_EINVAL, "null pointer");
+  float* part = nullptr;
+  const tbp_status r = static_scratch(&part);
+  if (r != TBP_OK) return r;
+  // nothing in the scratch has to start at zero: the row kernel writes every partial row that the column sum then reads
+  TBP_HIP(tbp::rmsnorm_p1(dtype, rows, d, eps, dy, x, g, resid, dx, dg_out, part, static_cast<hipStream_t>(stream)));
   return TBP_OK;
 }
 

@@ -150,6 +150,11 @@ def test_single_op_argument_checks():
     assert L.tbp_softmax_fwd(1, 1, 8192, 1, fake, fake, None) == 1
     assert L.tbp_rope(1, 4, 8, 2, 24, 48, fake, 0, fake, None) == 1
     assert L.tbp_rmsnorm_p1_scratch_bytes(4096) == 256 * 4096 * 4
+    # the variant with the library's static scratch refuses widths its array was not built for, before any device call
+    assert L.tbp_rmsnorm_p1_static(1, 4, 8200, 1e-6, fake, fake, fake, None, fake, fake, None) == 1
+    assert b"static scratch" in L.tbp_last_error()
+    assert L.tbp_rmsnorm_p1_static(0, 4, 4100, 1e-6, fake, fake, fake, None, fake, fake, None) == 1
+    assert L.tbp_rmsnorm_p1_static(1, 4, 4096, 1e-6, fake, fake, fake, None, None, fake, None) == 1      # null dx
     # leading dimensions beyond what the kernels' buffer ranges address are refused, not wrapped
     assert L.tbp_gemm(1, 0, 64, 64, 64, 1.0, fake, 1 << 22, fake, 64, fake, 64, 0, 0, None, None) == 1
     assert L.tbp_attention_fwd(1, 1, 2, 4096, 64, 1, fake, 1 << 19, fake, 128, fake, None) == 1
