@@ -76,8 +76,9 @@ typedef enum { TBP_ATTN_AUTO = 0, TBP_ATTN_MATERIALISED = 1, TBP_ATTN_FUSED = 2 
 
 /* Where the gradient of an RMSNorm gain, dg = sum over tokens of dy * x * rsqrt(mean(x^2) + eps), is computed.  A gain
  * is a parameter, so by Section 3.1 its gradient is backward-p2 work; the two settings give the same result:
- *   PARTIALS  p1, which has x and dy in registers anyway, leaves one fp32 [d_model] partial per norm and micro-batch
- *             in the stash and p2 adds the partials of its set (no activation is kept for the norms past p1);
+ *   PARTIALS  p1, which has x and dy in registers anyway, leaves the gain gradient of each norm and micro-batch in the
+ *             stash as at most 256 fp32 partial rows [d_model] (one per workgroup of its row kernel) and p2 adds up
+ *             the partial rows of its set (no activation is kept for the norms past p1);
  *   LITERAL   p1 computes nothing for the gains; each norm's input x and output derivative dy are stashed until p2
  *             like a linear layer's operands (4 more [tokens, d_model] tensors per layer and micro-batch, 2 for an
  *             MLP-only layer) and p2 computes dg from them, over the concatenated rows for KCONCAT. */
@@ -192,8 +193,19 @@ tbp_status tbp_gemm_ws(int dtype, int layout, int M, int N, int K, float alpha, 
                        void* workspace, size_t workspace_bytes, void* stream);
 tbp_status tbp_rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, const void* g, void* y,
                            void* stream);
-/* dx = resid + dL/dx of RMSNorm (resid may be NULL); dg_out [d] fp32 = sum_t dy x r (overwritten).
- * scratch: device, >= tbp_rmsnorm_p1_scratch_bytes(d). */
+/* RMSNorm backward, split as Section 3.1 splits every parametrised module.  The backward-p1 half,
+ * tbp_rmsnorm_p1_partials: dx = resid + dL/dx (resid may be NULL), and the gain gradient dg = sum over rows of
+ * dy * x * rsqrt(mean(x^2) + eps) is left as tbp_rmsnorm_partial_rows(dtype, rows, d) partial rows (at most 256; a
+ * function of the three arguments only) in partials_out [partial rows][d] fp32, each the sum over a fixed subset of the
+ * rows.  The backward-p2 half, tbp_gain_partials_sum: dg_out [d] fp32 (= or +=) the sum of the first n_rows rows of
+ * partials [n_rows][d] (partial rows of several micro-batches stored one after the other are summed in one call).
+ * This is how the stage computes the gain gradients with TBP_GAIN_PARTIALS.  rows == 0 writes nothing. */
+int tbp_rmsnorm_partial_rows(int dtype, int rows, int d);
+tbp_status tbp_rmsnorm_p1_partials(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
+                                   const void* resid, void* dx, float* partials_out, void* stream);
+tbp_status tbp_gain_partials_sum(const float* partials, int n_rows, int d, int accumulate, float* dg_out, void* stream);
+/* Both halves in one call: dx as above and dg_out [d] fp32 = the gain gradient (overwritten).
+ * scratch: device, >= tbp_rmsnorm_p1_scratch_bytes(d) (receives the partial rows). */
 tbp_status tbp_rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
                           const void* resid, void* dx, float* dg_out, void* scratch, void* stream);
 size_t tbp_rmsnorm_p1_scratch_bytes(int d);

@@ -12,7 +12,7 @@ import torch
 
 __all__ = [
     "TBP_F32", "TBP_BF16", "TBP_P2_LOOP", "TBP_P2_KCONCAT", "TBP_ATTN_AUTO", "TBP_ATTN_MATERIALISED", "TBP_ATTN_FUSED", "TBP_GAIN_PARTIALS", "TBP_GAIN_LITERAL", "NN", "NT", "TN", "TbpError", "lib", "library_path",
-    "tbp_config", "tbp_stash_query", "Stage", "tbp_gemm", "tbp_rmsnorm_fwd", "tbp_rmsnorm_p1", "tbp_rmsnorm_p1_static", "tbp_rmsnorm_gain_p2", "tbp_swiglu_fwd",
+    "tbp_config", "tbp_stash_query", "Stage", "tbp_gemm", "tbp_rmsnorm_fwd", "tbp_rmsnorm_p1", "tbp_rmsnorm_p1_partials", "tbp_gain_partials_sum", "tbp_rmsnorm_p1_static", "tbp_rmsnorm_gain_p2", "tbp_swiglu_fwd",
     "tbp_swiglu_p1", "tbp_rope_table", "tbp_rope", "tbp_softmax_fwd", "tbp_softmax_p1", "tbp_version",
     "tbp_attention_fwd", "tbp_attention_p1",
     "config_from_shape",
@@ -80,6 +80,9 @@ def lib() -> C.CDLL:
         L.tbp_gemm_workspace_bytes.restype = C.c_size_t
         L.tbp_rmsnorm_fwd.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float] + [C.c_void_p] * 4
         L.tbp_rmsnorm_p1.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float] + [C.c_void_p] * 8
+        L.tbp_rmsnorm_partial_rows.argtypes = [C.c_int] * 3
+        L.tbp_rmsnorm_p1_partials.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float] + [C.c_void_p] * 7
+        L.tbp_gain_partials_sum.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.tbp_rmsnorm_p1_static.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float] + [C.c_void_p] * 7
         L.tbp_swiglu_fwd.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 3
         L.tbp_swiglu_p1.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 4
@@ -276,6 +279,26 @@ def tbp_rmsnorm_p1(dy, x, g, eps, resid=None):
     _check(lib().tbp_rmsnorm_p1(_dt(x), rows, d, eps, _ptr(dy), _ptr(x), _ptr(g), _ptr(resid), _ptr(dx), _ptr(dg),
                                 _ptr(scratch), _stream()))
     return dx, dg
+
+
+def tbp_rmsnorm_p1_partials(dy, x, g, eps, resid=None):
+    """-> (dx, partial rows [tbp_rmsnorm_partial_rows, d] fp32 of the gain gradient)."""
+    rows, d = x.shape
+    dx = torch.empty_like(x)
+    parts = torch.empty((lib().tbp_rmsnorm_partial_rows(_dt(x), rows, d), d), dtype=torch.float32, device=x.device)
+    _check(lib().tbp_rmsnorm_p1_partials(_dt(x), rows, d, eps, _ptr(dy), _ptr(x), _ptr(g), _ptr(resid), _ptr(dx),
+                                         C.c_void_p(parts.data_ptr()), _stream()))
+    return dx, parts
+
+
+def tbp_gain_partials_sum(parts, dg=None):
+    """dg (new, or += into the given fp32 vector) = column sums of parts [n_rows, d]."""
+    n_rows, d = parts.shape
+    accumulate = dg is not None
+    if dg is None:
+        dg = torch.empty(d, dtype=torch.float32, device=parts.device)
+    _check(lib().tbp_gain_partials_sum(_ptr(parts), n_rows, d, 1 if accumulate else 0, C.c_void_p(dg.data_ptr()), _stream()))
+    return dg
 
 
 def tbp_rmsnorm_p1_static(dy, x, g, eps, resid=None, dx=None, dg=None):

@@ -583,12 +583,8 @@ template <int DH>
 static hipError_t launch_fwd(const AttnParams& p, hipStream_t s) {
   constexpr size_t smem = 2 * 2 * 64 * DH * 2;
   auto kern = attn_fwd_kernel<DH>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static AttrOnce once;
+  if (hipError_t e = once.set(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(p.H * p.B), (unsigned)((p.S + 127) / 128)), dim3(256), smem, s, p);
   return hipGetLastError();
 }
@@ -609,12 +605,8 @@ template <int DH>
 static hipError_t launch_bwd_kv_split(const AttnBwdParams& p, hipStream_t s) {
   constexpr size_t smem = 3 * (2 * 64 * DH * 2 + 1024) + 2 * 4 * 4096 + 4 * 32 * 144;     // three slots, two hand-over buffers, dS^T staging
   auto kern = attn_bwd_kv_split_kernel<DH>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static AttrOnce once;
+  if (hipError_t e = once.set(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(p.H * p.B), (unsigned)((p.S + 127) / 128)), dim3(512), smem, s, p);
   return hipGetLastError();
 }

@@ -128,16 +128,16 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(int rows, int d, float
 // per workgroup, which colsum_kernel adds up.
 // GAIN_ONLY (the gain gradient as a backward-p2 operation): only x and dy are read, and only the partials written.
 // partials == nullptr (backward-p1 of a stage that computes the gain gradient in p2): nothing is written for the gain.
-template <typename T, int MAXC, int WPR, bool GAIN_ONLY = false>
-__global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float eps, const T* __restrict__ dy,
+template <typename T, int MAXC, int WPR, bool GAIN_ONLY = false, int NW = 8>
+__global__ __launch_bounds__(64 * NW) void rmsnorm_p1_kernel(int rows, int d, float eps, const T* __restrict__ dy,
                                                          const T* __restrict__ x, const T* __restrict__ g,
                                                          const T* __restrict__ resid, T* __restrict__ dx,
                                                          float* __restrict__ partials) {
-  constexpr int N = Vec<T>::N, G = 8 / WPR, TPR = 64 * WPR;     // groups per workgroup, threads per row
+  constexpr int N = Vec<T>::N, G = NW / WPR, TPR = 64 * WPR;     // groups per workgroup, threads per row
   typedef typename Vec<T>::Raw Raw;
-  extern __shared__ float lds[];              // [2][8 waves][2 sums] reduction slots, then [d] column buffer
+  extern __shared__ float lds[];              // [2][NW waves][2 sums] reduction slots, then [d] column buffer
   float* const red = lds;
-  float* const colbuf = lds + 32;
+  float* const colbuf = lds + 4 * NW;
   const int wave = threadIdx.x >> 6, grp = wave / WPR, t = threadIdx.x - grp * TPR;
   const int nchunk = d / N;
   float cacc[MAXC][N];
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float 
     s_xx = wave_sum(s_xx);
     if constexpr (!GAIN_ONLY) s_yx = wave_sum(s_yx);
     if constexpr (WPR > 1) {                  // two slot sets used alternately: one barrier per row is enough
-      float* const slot = red + (it & 1) * 16;
+      float* const slot = red + (it & 1) * 2 * NW;
       if ((threadIdx.x & 63) == 0) {
         slot[wave * 2] = s_xx;
         slot[wave * 2 + 1] = s_yx;
@@ -254,36 +254,170 @@ __global__ __launch_bounds__(512) void rmsnorm_p1_kernel(int rows, int d, float 
     }
     __syncthreads();
   }
-  for (int col = threadIdx.x; col < d; col += 512) partials[(long)blockIdx.x * d + col] = colbuf[col];
+  for (int col = threadIdx.x; col < d; col += 64 * NW) partials[(long)blockIdx.x * d + col] = colbuf[col];
 }
 
-// out[col] (= or +=) sum_r parts[row_r][col]; rows given by value (host list) or the first n_first_rows rows.
-// A workgroup covers kColsumCols columns with 16 row lanes each (64-byte reads of rows that sit in the L2, which the
-// producing kernel has just written; 16 partial sums folded in LDS in a fixed order, so the result is reproducible).
+// The same operation with a deeper request queue.  WPR waves share a row (64 * WPR lanes, MAXC vectors per lane and
+// tensor), G = NW / WPR rows are in work per workgroup, and every lane keeps the x, dy and residual vectors of its
+// next PD rows in a register ring: a row's loads are issued PD iterations before the row is reduced, so each compute
+// unit has G * PD rows (24 KiB each at d = 4096) in flight at all times instead of G, which is what a memory system
+// with several microseconds of loaded latency needs to stay busy.  The lane's slice of the gain vector stays unpacked
+// in registers for the whole kernel (a lane owns the same columns in every row).  Reductions and the fold of the gain
+// gradient's column partials are those of the kernel above.
+template <typename T, int MAXC, int WPR, bool GAIN_ONLY, int NW, int PD>
+__global__ __launch_bounds__(64 * NW) void rmsnorm_p1_ring_kernel(int rows, int d, float eps, const T* __restrict__ dy,
+                                                                  const T* __restrict__ x, const T* __restrict__ g,
+                                                                  const T* __restrict__ resid, T* __restrict__ dx,
+                                                                  float* __restrict__ partials) {
+  constexpr int N = Vec<T>::N, G = NW / WPR, TPR = 64 * WPR;
+  typedef typename Vec<T>::Raw Raw;
+  extern __shared__ float lds[];              // [2][NW waves][2 sums] reduction slots, then [d] column buffer
+  float* const red = lds;
+  float* const colbuf = lds + 4 * NW;
+  const int wave = threadIdx.x >> 6, grp = wave / WPR, t = threadIdx.x - grp * TPR;
+  const int nchunk = d / N;
+  float cacc[MAXC][N], gv[MAXC][N];
+#pragma unroll
+  for (int c = 0; c < MAXC; c++) {
+#pragma unroll
+    for (int i = 0; i < N; i++) { cacc[c][i] = 0.f; gv[c][i] = 0.f; }
+    if constexpr (!GAIN_ONLY) {
+      const int ch = t + TPR * c;
+      if (ch < nchunk) Vec<T>::load(g + ch * N, gv[c]);
+    }
+  }
+  const int stride = G * (int)gridDim.x;
+  const int iters = (rows + stride - 1) / stride;
+  Raw xq[PD][MAXC], yq[PD][MAXC], rq[PD][MAXC];
+  auto fetch = [&](int it, Raw* xv, Raw* yv, Raw* rv) {
+    const int row = (it * (int)gridDim.x + (int)blockIdx.x) * G + grp;
+    if (it < iters && row < rows) {
+      const long base = (long)row * d;
+#pragma unroll
+      for (int c = 0; c < MAXC; c++) {
+        const int ch = t + TPR * c;
+        if (ch < nchunk) {
+          xv[c] = Vec<T>::load_raw(x + base + ch * N);
+          yv[c] = Vec<T>::load_raw(dy + base + ch * N);
+          if (!GAIN_ONLY && resid) rv[c] = Vec<T>::load_raw(resid + base + ch * N);
+        }
+      }
+    }
+  };
+#pragma unroll
+  for (int p = 0; p < PD; p++) fetch(p, xq[p], yq[p], rq[p]);
+  for (int it0 = 0; it0 < iters; it0 += PD) {
+#pragma unroll
+    for (int p = 0; p < PD; p++) {
+      const int it = it0 + p;
+      if (it >= iters) break;                 // (uniform over the workgroup)
+      const int row = (it * (int)gridDim.x + (int)blockIdx.x) * G + grp;
+      const bool live = row < rows;
+      const long base = (long)row * d;
+      Raw xr[MAXC], yr[MAXC], rr[MAXC];
+#pragma unroll
+      for (int c = 0; c < MAXC; c++) { xr[c] = xq[p][c]; yr[c] = yq[p][c]; rr[c] = rq[p][c]; }
+      fetch(it + PD, xq[p], yq[p], rq[p]);
+      float s_xx = 0.f, s_yx = 0.f;
+#pragma unroll
+      for (int c = 0; c < MAXC; c++) {
+        const int ch = t + TPR * c;
+        if (live && ch < nchunk) {
+          float xv[N], yv[N];
+          Vec<T>::unpack(xr[c], xv);
+          Vec<T>::unpack(yr[c], yv);
+#pragma unroll
+          for (int i = 0; i < N; i++) {
+            s_xx += xv[i] * xv[i];
+            if constexpr (!GAIN_ONLY) s_yx += yv[i] * gv[c][i] * xv[i];
+          }
+        }
+      }
+      s_xx = wave_sum(s_xx);
+      if constexpr (!GAIN_ONLY) s_yx = wave_sum(s_yx);
+      if constexpr (WPR > 1) {                // two slot sets used alternately: one barrier per row is enough
+        float* const slot = red + (it & 1) * 2 * NW;
+        if ((threadIdx.x & 63) == 0) {
+          slot[wave * 2] = s_xx;
+          slot[wave * 2 + 1] = s_yx;
+        }
+        __syncthreads();
+        s_xx = 0.f; s_yx = 0.f;
+#pragma unroll
+        for (int w = 0; w < WPR; w++) {
+          s_xx += slot[(grp * WPR + w) * 2];
+          s_yx += slot[(grp * WPR + w) * 2 + 1];
+        }
+      }
+      const float r = rsqrtf(s_xx / (float)d + eps);
+      const float coef = r * r * r * (s_yx / (float)d);
+#pragma unroll
+      for (int c = 0; c < MAXC; c++) {
+        const int ch = t + TPR * c;
+        if (live && ch < nchunk) {
+          float xv[N], yv[N];
+          Vec<T>::unpack(xr[c], xv);
+          Vec<T>::unpack(yr[c], yv);
+#pragma unroll
+          for (int i = 0; i < N; i++) cacc[c][i] += yv[i] * xv[i] * r;
+          if constexpr (!GAIN_ONLY) {
+            float o[N];
+            if (resid) Vec<T>::unpack(rr[c], o);
+            else {
+#pragma unroll
+              for (int i = 0; i < N; i++) o[i] = 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < N; i++) o[i] += r * yv[i] * gv[c][i] - xv[i] * coef;
+            Vec<T>::store(dx + base + ch * N, o);
+          }
+        }
+      }
+    }
+  }
+  if (!partials) return;                      // (uniform over the grid)
+  __syncthreads();
+  for (int gi = 0; gi < G; gi++) {
+    if (grp == gi) {
+#pragma unroll
+      for (int c = 0; c < MAXC; c++) {
+        const int ch = t + TPR * c;
+        if (ch < nchunk) {
+#pragma unroll
+          for (int i = 0; i < N; i++) {
+            const int col = ch * N + i;
+            colbuf[col] = (gi == 0 ? 0.f : colbuf[col]) + cacc[c][i];
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  for (int col = threadIdx.x; col < d; col += 64 * NW) partials[(long)blockIdx.x * d + col] = colbuf[col];
+}
+
+// out[col] (= or +=) sum over the first n_rows rows of parts[row][col].
+// A workgroup covers kColsumCols columns with 16 row lanes each (64-byte reads; 16 partial sums folded in LDS in a
+// fixed order, so the result is reproducible).
 constexpr int kColsumCols = 16;
-struct RowList { int n; int idx[64]; };
-__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ parts, RowList rl, int n_first_rows,
-                                                     int d, int accumulate, float* __restrict__ out) {
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ parts, int n_rows, int d, int accumulate,
+                                                     float* __restrict__ out) {
   __shared__ float fold[16][kColsumCols + 1];
   const int c = threadIdx.x & (kColsumCols - 1), rlane = threadIdx.x / kColsumCols;
   const int col = blockIdx.x * kColsumCols + c;
   float s = 0.f;
   if (col < d) {
-    if (n_first_rows > 0) {
-      // four independent chains per lane (rows r, r + 16, r + 32, r + 48 of each group of 64): the loads of a group
-      // are in flight together instead of one after the other; the chains are added in a fixed order
-      float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-      int r = rlane;
-      for (; r + 48 < n_first_rows; r += 64) {
-        const float v0 = parts[(long)r * d + col], v1 = parts[(long)(r + 16) * d + col];
-        const float v2 = parts[(long)(r + 32) * d + col], v3 = parts[(long)(r + 48) * d + col];
-        a0 += v0; a1 += v1; a2 += v2; a3 += v3;
-      }
-      for (; r < n_first_rows; r += 16) a0 += parts[(long)r * d + col];
-      s = (a0 + a1) + (a2 + a3);
-    } else {
-      for (int r = rlane; r < rl.n; r += 16) s += parts[(long)rl.idx[r] * d + col];
+    // four independent chains per lane (rows r, r + 16, r + 32, r + 48 of each group of 64): the loads of a group
+    // are in flight together instead of one after the other; the chains are added in a fixed order
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int r = rlane;
+    for (; r + 48 < n_rows; r += 64) {
+      const float v0 = parts[(long)r * d + col], v1 = parts[(long)(r + 16) * d + col];
+      const float v2 = parts[(long)(r + 32) * d + col], v3 = parts[(long)(r + 48) * d + col];
+      a0 += v0; a1 += v1; a2 += v2; a3 += v3;
     }
+    for (; r < n_rows; r += 16) a0 += parts[(long)r * d + col];
+    s = (a0 + a1) + (a2 + a3);
   }
   fold[rlane][c] = s;
   __syncthreads();
@@ -592,82 +726,111 @@ hipError_t rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, con
   return dtype ? rmsnorm_fwd_t<bf16_t>(rows, d, eps, x, g, y, s) : rmsnorm_fwd_t<float>(rows, d, eps, x, g, y, s);
 }
 
-template <typename T, int WPR, bool GAIN_ONLY = false>
+// Which kernel a (storage type, width) pair runs on, and how many rows a workgroup has in work at a time.  The number
+// of workgroups, which is the number of partial rows of the gain gradient that the row kernel leaves, follows from it.
+struct NormPlan { int kind, wpr, rows_per_block; };      // kind 0: rmsnorm_p1_kernel with `wpr` waves per row; 1: ring kernel
+#ifndef TBP_RING_NW1
+#define TBP_RING_NW1 16
+#endif
+#ifndef TBP_RING_PD1
+#define TBP_RING_PD1 2
+#endif
+#ifndef TBP_RING_PD2
+#define TBP_RING_PD2 2
+#endif
+static NormPlan norm_plan(int dtype, int d) {
+  const int wc = (d / (dtype ? 8 : 4) + 63) / 64;   // vectors per lane if one wave owned a whole row
+  if (dtype) {
+    // bf16 rows of more than 2048 columns (the 7B and 13B widths among them) run on the ring kernel, 8 waves per row:
+    // up to 4096 columns one vector per lane and two rows per 1024-thread workgroup; wider rows two vectors per lane
+    // and one row per 512-thread workgroup (two vectors per lane in 1024 threads do not fit the register file)
+    if (wc > 4) return NormPlan{1, 8, wc <= 8 ? TBP_RING_NW1 / 8 : 1};
+    return NormPlan{0, 1, 8};
+  }
+  const int wpr = wc <= 4 ? 1 : wc <= 8 ? 2 : wc <= 16 ? 4 : 8;
+  return NormPlan{0, wpr, 8 / wpr};
+}
+int rmsnorm_partial_rows(int dtype, int rows, int d) {
+  if (rows <= 0 || d <= 0) return 0;
+  const int g = norm_plan(dtype, d).rows_per_block;
+  const int nblk = (rows + g - 1) / g;
+  return nblk < kNormPartialBlocks ? nblk : kNormPartialBlocks;
+}
+
+template <typename T, int WPR, bool GAIN_ONLY>
 static hipError_t rmsnorm_p1_w(int rows, int d, float eps, const T* dy, const T* x, const T* g, const T* resid, T* dx,
-                               float* partials, int* nblk_out, hipStream_t s) {
-  constexpr int G = 8 / WPR;
+                               float* partials, int nblk, hipStream_t s) {
+  constexpr int NW = 8;
   const int c = (d / Vec<T>::N + 64 * WPR - 1) / (64 * WPR);      // vectors per lane
-  int nblk = (rows + G - 1) / G;
-  if (nblk > kNormPartialBlocks) nblk = kNormPartialBlocks;
-  *nblk_out = nblk;
-  const size_t smem = (32 + (size_t)d) * sizeof(float);
-  const dim3 grid(nblk), block(512);
-  if (c <= 1) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 1, WPR, GAIN_ONLY>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
-  else if (c <= 2) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 2, WPR, GAIN_ONLY>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
-  else if (c <= 4) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 4, WPR, GAIN_ONLY>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
+  const size_t smem = (4 * NW + (size_t)d) * sizeof(float);
+  const dim3 grid(nblk), block(64 * NW);
+  if (c <= 1) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 1, WPR, GAIN_ONLY, NW>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
+  else if (c <= 2) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 2, WPR, GAIN_ONLY, NW>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
+  else if (c <= 4) hipLaunchKernelGGL((rmsnorm_p1_kernel<T, 4, WPR, GAIN_ONLY, NW>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
-template <typename T, bool GAIN_ONLY = false>
-static hipError_t rmsnorm_p1_t(int rows, int d, float eps, const void* dy, const void* x, const void* g,
-                               const void* resid, void* dx, int accumulate, float* dg_out, float* partials,
-                               hipStream_t s) {
-  auto DY = (const T*)dy; auto X = (const T*)x; auto G = (const T*)g; auto RS = (const T*)resid; auto DX = (T*)dx;
-  const int wc = (d / Vec<T>::N + 63) / 64;         // vectors per lane if one wave owned a whole row
-  int nblk = 0;
-  hipError_t e;
-  float* const parts = dg_out ? partials : nullptr;
-  if (wc <= 4) e = rmsnorm_p1_w<T, 1, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, parts, &nblk, s);
-  else if (wc <= 8) e = rmsnorm_p1_w<T, 2, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, parts, &nblk, s);
-  else if (wc <= 16) e = rmsnorm_p1_w<T, 4, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, parts, &nblk, s);
-  else e = rmsnorm_p1_w<T, 8, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, parts, &nblk, s);
-  if (e != hipSuccess || !dg_out) return e;
-  RowList rl{};
-  hipLaunchKernelGGL(colsum_kernel, dim3((d + kColsumCols - 1) / kColsumCols), dim3(256), 0, s, (const float*)partials, rl, nblk, d,
-                     accumulate, dg_out);
+template <typename T, bool GAIN_ONLY>
+static hipError_t rmsnorm_p1_ring(int rows, int d, float eps, const T* dy, const T* x, const T* g, const T* resid, T* dx,
+                                  float* partials, int nblk, hipStream_t s) {
+  constexpr int WPR = 8;
+  const int c = (d / Vec<T>::N + 64 * WPR - 1) / (64 * WPR);      // vectors per lane
+  if (c > 2) return hipErrorInvalidValue;
+  const int NW = c == 1 ? TBP_RING_NW1 : 8;
+  const size_t smem = (4 * NW + (size_t)d) * sizeof(float);
+  const dim3 grid(nblk), block(64 * NW);
+  if (c == 1) hipLaunchKernelGGL((rmsnorm_p1_ring_kernel<T, 1, WPR, GAIN_ONLY, TBP_RING_NW1, TBP_RING_PD1>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
+  else hipLaunchKernelGGL((rmsnorm_p1_ring_kernel<T, 2, WPR, GAIN_ONLY, 8, TBP_RING_PD2>), grid, block, smem, s, rows, d, eps, dy, x, g, resid, dx, partials);
   return hipGetLastError();
 }
+
+// The row kernel alone: dx (unless GAIN_ONLY) and, if `partials` is given, rmsnorm_partial_rows(...) partial rows of
+// the gain gradient.
+template <typename T, bool GAIN_ONLY>
+static hipError_t rmsnorm_rows_t(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
+                                 const void* resid, void* dx, float* partials, hipStream_t s) {
+  auto DY = (const T*)dy; auto X = (const T*)x; auto G = (const T*)g; auto RS = (const T*)resid; auto DX = (T*)dx;
+  const NormPlan pl = norm_plan(dtype, d);
+  const int nblk = rmsnorm_partial_rows(dtype, rows, d);
+  if constexpr (sizeof(T) == 2) {
+    if (pl.kind == 1) return rmsnorm_p1_ring<T, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, partials, nblk, s);
+  }
+  switch (pl.wpr) {
+    case 1: return rmsnorm_p1_w<T, 1, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, partials, nblk, s);
+    case 2: return rmsnorm_p1_w<T, 2, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, partials, nblk, s);
+    case 4: return rmsnorm_p1_w<T, 4, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, partials, nblk, s);
+    default: return rmsnorm_p1_w<T, 8, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, partials, nblk, s);
+  }
+}
+
+hipError_t gain_partials_sum(const float* partials, int n_rows, int d, int accumulate, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(colsum_kernel, dim3((d + kColsumCols - 1) / kColsumCols), dim3(256), 0, s, partials, n_rows > 0 ? n_rows : 0, d,
+                     accumulate, out);
+  return hipGetLastError();
+}
+
+hipError_t rmsnorm_p1_rows(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
+                           const void* resid, void* dx, float* partials, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  return dtype ? rmsnorm_rows_t<bf16_t, false>(dtype, rows, d, eps, dy, x, g, resid, dx, partials, s)
+               : rmsnorm_rows_t<float, false>(dtype, rows, d, eps, dy, x, g, resid, dx, partials, s);
+}
+
 hipError_t rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
                       const void* resid, void* dx, float* dg_out, float* partials, hipStream_t s) {
-  if (rows <= 0) {      // no rows: the gain gradient is zero (written by the same column-sum kernel)
-    if (!dg_out) return hipSuccess;
-    RowList none{};
-    hipLaunchKernelGGL(colsum_kernel, dim3((d + kColsumCols - 1) / kColsumCols), dim3(256), 0, s, (const float*)partials, none, 0, d, 0,
-                       dg_out);
-    return hipGetLastError();
-  }
-  return dtype ? rmsnorm_p1_t<bf16_t>(rows, d, eps, dy, x, g, resid, dx, 0, dg_out, partials, s)
-               : rmsnorm_p1_t<float>(rows, d, eps, dy, x, g, resid, dx, 0, dg_out, partials, s);
+  hipError_t e = rmsnorm_p1_rows(dtype, rows, d, eps, dy, x, g, resid, dx, dg_out ? partials : nullptr, s);
+  if (e != hipSuccess || !dg_out) return e;
+  return gain_partials_sum(partials, rmsnorm_partial_rows(dtype, rows, d), d, 0, dg_out, s);     // (no rows: zeros)
 }
 
 hipError_t rmsnorm_gain_p2(int dtype, int rows, int d, float eps, const void* dy, const void* x, int accumulate,
                            float* dg_out, float* partials, hipStream_t s) {
-  if (rows <= 0) {
-    if (accumulate) return hipSuccess;
-    RowList none{};
-    hipLaunchKernelGGL(colsum_kernel, dim3((d + kColsumCols - 1) / kColsumCols), dim3(256), 0, s, (const float*)partials, none, 0, d, 0,
-                       dg_out);
-    return hipGetLastError();
-  }
-  return dtype ? rmsnorm_p1_t<bf16_t, true>(rows, d, eps, dy, x, nullptr, nullptr, nullptr, accumulate, dg_out, partials, s)
-               : rmsnorm_p1_t<float, true>(rows, d, eps, dy, x, nullptr, nullptr, nullptr, accumulate, dg_out, partials, s);
-}
-
-hipError_t gain_grad_sum(const float* parts, const int* rows_host, int n, int d, int accumulate, float* out,
-                         hipStream_t s) {
-  int done = 0;
-  do {
-    RowList rl{};
-    rl.n = (n - done) < 64 ? (n - done) : 64;
-    for (int i = 0; i < rl.n; i++) rl.idx[i] = rows_host[done + i];
-    hipLaunchKernelGGL(colsum_kernel, dim3((d + kColsumCols - 1) / kColsumCols), dim3(256), 0, s, parts, rl, 0, d,
-                       (accumulate || done > 0) ? 1 : 0, out);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    done += rl.n;
-  } while (done < n);
-  return hipSuccess;
+  if (rows <= 0) return accumulate ? hipSuccess : gain_partials_sum(partials, 0, d, 0, dg_out, s);
+  hipError_t e = dtype ? rmsnorm_rows_t<bf16_t, true>(dtype, rows, d, eps, dy, x, nullptr, nullptr, nullptr, partials, s)
+                       : rmsnorm_rows_t<float, true>(dtype, rows, d, eps, dy, x, nullptr, nullptr, nullptr, partials, s);
+  if (e != hipSuccess) return e;
+  return gain_partials_sum(partials, rmsnorm_partial_rows(dtype, rows, d), d, accumulate, dg_out, s);
 }
 
 static inline unsigned grid_for(long nvec) {

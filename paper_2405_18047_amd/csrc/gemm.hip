@@ -351,9 +351,17 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   // and a wave-wide store covers whole rows of the tile.
   if constexpr (SPLIT) {
     // Partial sums meet in memory: every workgroup of a tile leaves its accumulators there in register order (lane-
-    // contiguous 16-byte stores), makes them visible and takes a ticket; the one that draws the last ticket adds all
-    // slices up in slice order, clears the counter for the next product and goes on to the epilogue.  Nobody waits
-    // for anybody: a workgroup that is not last is simply done.
+    // contiguous stores), takes a ticket, and the one that draws the last ticket adds all slices up in slice order,
+    // clears the counter for the next product and goes on to the epilogue.  Nobody waits for anybody: a workgroup that
+    // is not last is simply done.
+    // The exchange does not depend on where the workgroups run.  The partial sums are written and read with
+    // device-scope accesses (relaxed atomic stores / loads: they go through to, and come from, the level of the memory
+    // system that all XCDs share, whatever L2 the workgroup sits behind) and the ticket is a device-scope atomic.
+    // Order: every lane waits until its own stores have completed (vmcnt(0)), the workgroup barrier collects all
+    // lanes, only then does lane 0 take the ticket; a workgroup that sees the last ticket therefore follows, in
+    // time, the completion of every slice's stores, and its loads cannot be served from a stale cached copy.  No
+    // cache-wide write-back or invalidate is involved (such a fence would flush the L2 under every other workgroup's
+    // operand panels).  The launch map still puts the slices of a tile on one XCD, but only for speed.
     constexpr long TILE = (long)BM * BN;
     float* const mine = p.split_ws + ((long)tile_seq * p.split + split_idx) * TILE;
 #pragma unroll
@@ -361,23 +369,17 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
 #pragma unroll
       for (int j = 0; j < TN; j++)
 #pragma unroll
-        for (int e4 = 0; e4 < 4; e4++) {
-          f32x4 v;
-#pragma unroll
-          for (int q = 0; q < 4; q++) v[q] = acc[i][j][4 * e4 + q];
-          *reinterpret_cast<f32x4*>(mine + ((((i * TN + j) * 4 + e4) * 256 + tid) << 2)) = v;
-        }
-    // All slices of a tile run on one XCD (see the launch map), so the partial sums only have to reach that XCD's L2,
-    // which stores do before the wave's memory counter lets go of them; a device-wide fence here would write back and
-    // invalidate the whole L2 under every other workgroup's operands.  The readers' vector caches cannot hold these
-    // lines: each is written once and read once per launch, and a launch starts with clean vector caches.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        for (int e = 0; e < 16; e++)
+          __hip_atomic_store(mine + ((i * TN + j) * 16 + e) * 256 + tid, acc[i][j][e], __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+    wait_vmem<0>();                         // this lane's partial sums have been written
     LDS_AS int* const last_arrival = reinterpret_cast<LDS_AS int*>(lds);     // (the ring is free once all waves are here)
     __syncthreads();
-    if (tid == 0) *last_arrival = atomicAdd(p.split_cnt + tile_seq, 1u) == (unsigned)(p.split - 1);
+    if (tid == 0)
+      *last_arrival = __hip_atomic_fetch_add(p.split_cnt + tile_seq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                      (unsigned)(p.split - 1);
     __syncthreads();
     if (!*last_arrival) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 #pragma unroll
     for (int i = 0; i < TM; i++)
 #pragma unroll
@@ -391,13 +393,11 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
 #pragma unroll
         for (int j = 0; j < TN; j++)
 #pragma unroll
-          for (int e4 = 0; e4 < 4; e4++) {
-            const f32x4 v = *reinterpret_cast<const f32x4*>(part + ((((i * TN + j) * 4 + e4) * 256 + tid) << 2));
-#pragma unroll
-            for (int q = 0; q < 4; q++) acc[i][j][4 * e4 + q] += v[q];
-          }
+          for (int e = 0; e < 16; e++)
+            acc[i][j][e] += __hip_atomic_load(part + ((i * TN + j) * 16 + e) * 256 + tid, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (tid == 0) p.split_cnt[tile_seq] = 0u;
+    if (tid == 0) __hip_atomic_store(p.split_cnt + tile_seq, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();                          // every wave is done with the ring
   OutT* C = reinterpret_cast<OutT*>(p.C) + zo * p.sCo + zi * p.sCi;
@@ -546,9 +546,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_causal_pair_kernel(GemmParams p
   }
 }
 
-// `split` workgroups per output tile, each over its slice of the contraction.  The hardware hands consecutive
-// workgroup ids to the 8 XCDs in turn; ids that differ by 8 share an XCD, and those are made the slices of one tile, so
-// that the partial sums of a tile meet in one L2.
+// `split` workgroups per output tile, each over its slice of the contraction.  Workgroup ids that differ by 8 are made
+// the slices of one tile: where the hardware hands consecutive ids to the 8 XCDs in turn, a tile's slices then run
+// on one XCD and fetch the tile's operand panels through one L2 (a matter of speed only: the exchange of the partial
+// sums is correct wherever the workgroups run).
 template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD>
 __global__ __launch_bounds__(256) void gemm_bf16_splitk_kernel(GemmParams p) {
   const int v = (int)blockIdx.x, xcd = v & 7, q = v >> 3;
@@ -727,13 +728,8 @@ static hipError_t launch_bf16(const GemmParams& p0, int batch, hipStream_t s) {
   constexpr size_t smem = (size_t)(KD == 32 ? STAGES : 2) * (BM + BN) * KD * sizeof(bf16_t);
   static_assert(smem <= 160 * 1024, "LDS budget of one gfx950 compute unit");
   auto kern = gemm_bf16_kernel<BM, BN, AKC, BKC, OutT, KD>;
-  static bool attr_set = false;     // once per instantiation; harmless if two threads race
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static AttrOnce once;
+  if (hipError_t e = once.set(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
   unsigned nt = (unsigned)(p.tiles_m * p.tiles_n);
   if (batch > 1 && p.causal == CAUSAL_SKIP_UPPER && p.tiles_m == p.tiles_n)
     nt = (unsigned)(p.tiles_m * (p.tiles_m + 1) / 2);       // lower-triangular tiles only
@@ -750,13 +746,8 @@ static hipError_t launch_bf16_causal_pair(const GemmParams& p0, int batch, hipSt
   if (p.tiles_n != 1 || p.causal != CAUSAL_K_END) return hipErrorInvalidValue;
   constexpr size_t smem = (size_t)(KD == 32 ? STAGES : 2) * (BM + BN) * KD * sizeof(bf16_t);
   auto kern = gemm_bf16_causal_pair_kernel<BM, BN, AKC, BKC, OutT, KD>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static AttrOnce once;
+  if (hipError_t e = once.set(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)((p.tiles_m + 1) / 2), 1, (unsigned)batch), dim3(256), smem, s, p);
   return hipGetLastError();
 }
@@ -812,13 +803,8 @@ static hipError_t launch_bf16_split(const GemmParams& p0, int split, void* ws, i
   if ((size_t)tiles * sizeof(unsigned) > kSplitCounterBytes) return hipErrorInvalidValue;
   constexpr size_t smem = (size_t)(KD == 32 ? STAGES : 2) * (BM + BN) * KD * sizeof(bf16_t);
   auto kern = gemm_bf16_splitk_kernel<BM, BN, AKC, BKC, OutT, KD>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static AttrOnce once;
+  if (hipError_t e = once.set(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
   if (!counters_zero) {
     hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, s, p.split_cnt, (int)(kSplitCounterBytes / 4), 0u);
     hipError_t e = hipGetLastError();
@@ -835,26 +821,24 @@ static hipError_t launch_bf16_split(const GemmParams& p0, int split, void* ws, i
 #ifndef TBP_KC_DEPTH_SMALL
 #define TBP_KC_DEPTH_SMALL 32
 #endif
+#ifndef TBP_TN_DEPTH
+#define TBP_TN_DEPTH 32
+#endif
 template <int BM, int BN, typename OutT>
 static hipError_t dispatch_layout(int layout, const GemmParams& p, int batch, hipStream_t s) {
   constexpr int KD = BM >= 256 ? 64 : TBP_KC_DEPTH_SMALL;
   switch (layout) {
     case NN: return launch_bf16<BM, BN, true, false, OutT, KD>(p, batch, s);
     case NT: return launch_bf16<BM, BN, true, true, OutT, KD>(p, batch, s);
-    case TN: return launch_bf16<BM, BN, false, false, OutT, 32>(p, batch, s);
+    case TN: return launch_bf16<BM, BN, false, false, OutT, (BM >= 256 ? TBP_TN_DEPTH : 32)>(p, batch, s);
   }
   return hipErrorInvalidValue;
 }
 
 hipError_t gemm_tn_grouped(const GroupedProduct* prods, int n, hipStream_t s) {
   constexpr size_t smem = (size_t)STAGES * (256 + 256) * BK * sizeof(bf16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_grouped_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static AttrOnce once;
+  if (hipError_t e = once.set(reinterpret_cast<const void*>(gemm_tn_grouped_kernel), smem); e != hipSuccess) return e;
   for (int base = 0; base < n; base += kMaxGrouped) {
     GroupedTable g{};
     int blocks = 0;

@@ -93,10 +93,19 @@ struct GroupedTable {
 hipError_t gemm_tn_grouped(const GroupedProduct* prods, int n, hipStream_t s);
 
 hipError_t rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x, const void* g, void* y, hipStream_t s);
-constexpr int kNormPartialBlocks = 256;     // row-block partials of the gain gradient
+constexpr int kNormPartialBlocks = 256;     // at most this many row-block partials of the gain gradient per call
+// RMSNorm backward-p1.  The gain gradient dg = sum over rows of dy * x * r leaves the row kernel as
+// rmsnorm_partial_rows(dtype, rows, d) <= kNormPartialBlocks partial rows [d] fp32 (one per workgroup, each a sum over
+// that workgroup's rows in a fixed order); gain_partials_sum adds partial rows up.
+int rmsnorm_partial_rows(int dtype, int rows, int d);
+// dx = resid + dL/dx; partials (may be null: nothing is computed for the gain) receives the partial rows.
+hipError_t rmsnorm_p1_rows(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
+                           const void* resid, void* dx, float* partials, hipStream_t s);
+// out[d] (= or +=) sum of the first n_rows rows of partials [n_rows][d]  (n_rows == 0: zero, or out left alone)
+hipError_t gain_partials_sum(const float* partials, int n_rows, int d, int accumulate, float* out, hipStream_t s);
+// Both in one call: rows, then the sum into dg_out (dg_out == nullptr: nothing is computed for the gain).
 hipError_t rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
                       const void* resid, void* dx, float* dg_out, float* partials, hipStream_t s);
-// dg_out == nullptr in rmsnorm_p1: nothing is computed for the gain.
 hipError_t rmsnorm_gain_p2(int dtype, int rows, int d, float eps, const void* dy, const void* x, int accumulate,
                            float* dg_out, float* partials, hipStream_t s);
 hipError_t swiglu_fwd(int dtype, int rows, int f, const void* gu, void* m, hipStream_t s);
@@ -109,11 +118,6 @@ hipError_t softmax_p1(int dtype, long n_rows_total, int seq, int causal, const v
 // delta[t * n_heads + h] = sum_c a[t, h*dh + c] * b[t, h*dh + c]   (fp32; a, b are [rows, n_heads*head_dim])
 hipError_t head_rowdot(int dtype, int rows, int n_heads, int head_dim, const void* a, const void* b, float* delta,
                        hipStream_t s);
-// out[d] (= or +=) sum over n of parts[n][d] given as n separate pointers packed in a device-free way:
-// parts are rows of one fp32 matrix, selected by index list held in kernel arguments (n <= 64 per launch).
-hipError_t gain_grad_sum(const float* parts, const int* rows_host, int n, int d, int accumulate, float* out,
-                         hipStream_t s);
-
 // Fused attention (bf16 storage only, head_dim 64 or 128).  qkv: [batch*seq, ld_qkv] with column blocks q | k | v of
 // n_heads*head_dim each (q and k already rotated); out: [batch*seq, ld_out]; lse: [batch, n_heads, seq] fp32, the log2
 // of each row's sum of exp2(score / sqrt(head_dim) * log2 e).
@@ -131,6 +135,22 @@ hipError_t attention_p1(int batch, int n_heads, int seq, int head_dim, int causa
 // Register-resident MFMA loop (measurement aid): blocks x 4 waves x iters x 16 MFMAs of 32x32x16.
 // seed: 8 x 64 x 8 bf16 values; sink: blocks * 256 floats.
 hipError_t mfma_ceiling(int blocks, int iters, const void* seed, float* sink, hipStream_t s);
+
+// A kernel that wants more than 64 KiB of dynamic LDS must be told so once per DEVICE (the attribute belongs to the
+// kernel's image on that device).  One instance per kernel instantiation; racing threads repeat a harmless call.
+struct AttrOnce {
+  static constexpr int kMaxDev = 64;
+  bool done[kMaxDev] = {};
+  hipError_t set(const void* kern, size_t smem) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < kMaxDev && done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess && dev >= 0 && dev < kMaxDev) done[dev] = true;
+    return e;
+  }
+};
 
 // Limits enforced by the host before any launch.
 inline int max_d_model(int dtype) { return dtype == 1 ? 8192 : 4096; }

@@ -82,11 +82,12 @@ struct Layout {
   size_t w_layer_bytes;
   size_t a_off[A_COUNT];        // per (layer, slot)
   size_t a_slot_bytes;          // one slot of one layer
-  size_t gain_part_off;         // fp32 [L][2][Mmax][d] per-micro-batch gain-gradient partials (W class)
+  size_t gain_part_off;         // fp32 [L][2][Mmax][gain_rows][d]: per micro-batch, the partial rows of a norm's gain gradient (W class)
   size_t gain_part_bytes;
+  int gain_rows;                // partial rows that backward-p1 of one micro-batch leaves per norm
   size_t w_total, a_base, a_total, ws_base, ws_total, arena;
   // workspace pieces
-  size_t ws_t_f, ws_t_d0, ws_t_d1, ws_scores, ws_norm_partials, ws_norm_partials_p2, ws_rope, ws_delta, ws_split;
+  size_t ws_t_f, ws_t_d0, ws_t_d1, ws_scores, ws_norm_partials_p2, ws_rope, ws_delta, ws_split;
   size_t ws_split_bytes;        // scratch of the products that split their contraction (0: none does)
   // accounting units
   size_t w_fwd_bytes_per_mb, w_p1_bytes_per_mb, a_bytes_per_mb;
@@ -101,7 +102,8 @@ Layout plan(const Dims& c) {
   }
   y.w_layer_bytes = off;
   y.gain_part_off = y.w_layer_bytes * c.L;
-  y.gain_part_bytes = c.literal ? 0 : align_up((size_t)c.L * 2 * c.Mmax * c.d * sizeof(float), 256);
+  y.gain_rows = c.literal ? 0 : tbp::rmsnorm_partial_rows(c.dtype, c.T, c.d);
+  y.gain_part_bytes = align_up((size_t)c.L * 2 * c.Mmax * y.gain_rows * c.d * sizeof(float), 256);
   y.w_total = y.gain_part_off + y.gain_part_bytes;
   off = 0;
   for (int t = 0; t < A_COUNT; t++) {
@@ -119,7 +121,6 @@ Layout plan(const Dims& c) {
   // fp32 scores, then dS (materialised attention) or dS^T in the storage type (fused)
   y.ws_scores = off; off += !c.attn ? 0 : align_up(c.fused ? (size_t)c.B * c.H * tbp::attn_ds_elems(c.S) * c.e
                                                            : (size_t)c.B * c.H * c.S * c.S * sizeof(float), 256);
-  y.ws_norm_partials = off; off += align_up((size_t)tbp::kNormPartialBlocks * c.d * sizeof(float), 256);
   y.ws_norm_partials_p2 = off; off += c.literal ? align_up((size_t)tbp::kNormPartialBlocks * c.d * sizeof(float), 256) : 0;
   y.ws_rope = off; off += c.attn ? align_up((size_t)c.S * (c.dh / 2) * sizeof(float2), 256) : 0;
   y.ws_delta = off; off += c.attn ? align_up((size_t)c.T * c.H * sizeof(float), 256) : 0;
@@ -142,7 +143,7 @@ Layout plan(const Dims& c) {
     if (w_from_forward(t)) fw += b; else p1 += b;
   }
   y.w_fwd_bytes_per_mb = fw * c.L;
-  y.w_p1_bytes_per_mb = (p1 + (c.literal ? 0 : (c.attn ? 2 : 1) * (size_t)c.d * sizeof(float))) * c.L;
+  y.w_p1_bytes_per_mb = (p1 + (c.attn ? 2 : 1) * (size_t)y.gain_rows * c.d * sizeof(float)) * c.L;
   size_t a = 0;
   for (int t = 0; t < A_COUNT; t++) a += a_bytes(c, t);
   y.a_bytes_per_mb = a * c.L;
@@ -211,8 +212,8 @@ struct tbp_stage {
   void* aslot(int layer, int t, int slot) const {
     return arena + y.a_base + ((size_t)layer * c.slots + slot) * y.a_slot_bytes + y.a_off[t];
   }
-  float* gain_part(int layer, int which) const {      // [Mmax][d]
-    return reinterpret_cast<float*>(arena + y.gain_part_off) + ((size_t)layer * 2 + which) * c.Mmax * c.d;
+  float* gain_part(int layer, int which, int mb) const {      // [gain_rows][d] of micro-batch mb; consecutive micro-batches are consecutive rows
+    return reinterpret_cast<float*>(arena + y.gain_part_off) + (((size_t)layer * 2 + which) * c.Mmax + mb) * y.gain_rows * c.d;
   }
   void* ws(size_t off) const { return arena + y.ws_base + off; }
   // inputs of the two RMSNorms of a layer: forward->p1 slot, or a slab kept until p2 (literal gain gradient)
@@ -326,7 +327,6 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
   const Dims& c = st->c;
   const int dt = c.dtype, T = c.T, d = c.d, f = c.f;
   const size_t act_bytes = (size_t)T * d * c.e;
-  float* npart = (float*)st->ws(st->y.ws_norm_partials);
   // the stage's upstream gradient is the output derivative of the last layer's down projection: keep it
   TBP_HIP(hipMemcpyAsync(st->wslab(c.L - 1, W_DX2, mb), dy, act_bytes, hipMemcpyDeviceToDevice, s));
   for (int l = c.L - 1; l >= 0; l--) {
@@ -345,8 +345,9 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
     // dh2 = [dg, du] Wgu^T
     TBP_HIP(linear_gemm(st, gemm_args(tbp::NT, T, d, 2 * f, dgu, 2 * f, st->w_gu[l], 2 * f, dh, d), s));
     void* dx1 = c.attn ? st->wslab(l, W_DX1, mb) : dx_out;
-    TBP_HIP(tbp::rmsnorm_p1(dt, T, d, c.eps, dh, x1, st->g2[l], dx2, dx1,
-                            c.literal ? nullptr : st->gain_part(l, 1) + (size_t)mb * d, npart, s));
+    // (the partial rows of the gain gradient stay in the stash as they leave the row kernel: backward-p2 adds them up)
+    TBP_HIP(tbp::rmsnorm_p1_rows(dt, T, d, c.eps, dh, x1, st->g2[l], dx2, dx1,
+                                 c.literal ? nullptr : st->gain_part(l, 1, mb), s));
     if (!c.attn) continue;
     void* da = st->ws(st->y.ws_t_d1);
     void* qkv = st->aslot(l, A_QKV, slot);
@@ -408,8 +409,8 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
     // dh1 = [dq, dk, dv] Wqkv^T
     void* dh1 = c.literal ? st->wslab(l, W_N1DY, mb) : dh;
     TBP_HIP(linear_gemm(st, gemm_args(tbp::NT, T, d, 3 * d, dqkv, 3 * d, st->w_qkv[l], 3 * d, dh1, d), s));
-    TBP_HIP(tbp::rmsnorm_p1(dt, T, d, c.eps, dh1, x0, st->g1[l], dx1, dx_out,
-                            c.literal ? nullptr : st->gain_part(l, 0) + (size_t)mb * d, npart, s));
+    TBP_HIP(tbp::rmsnorm_p1_rows(dt, T, d, c.eps, dh1, x0, st->g1[l], dx1, dx_out,
+                                 c.literal ? nullptr : st->gain_part(l, 0, mb), s));
   }
   return TBP_OK;
 }
@@ -490,10 +491,17 @@ tbp_status run_p2(tbp_stage* st, const int* mbs, int n, int mode, int accumulate
       }
     return TBP_OK;
   }
-  for (int l = 0; l < c.L; l++) {
-    if (c.attn) TBP_HIP(tbp::gain_grad_sum(st->gain_part(l, 0), mbs, n, c.d, accumulate, st->dg1[l], s));
-    TBP_HIP(tbp::gain_grad_sum(st->gain_part(l, 1), mbs, n, c.d, accumulate, st->dg2[l], s));
-  }
+  // gain gradients: the partial rows that backward-p1 left, added up run by run of consecutive micro-batches (whose
+  // partial rows are consecutive in the stash; a K-concatenated set is one run)
+  for (int l = 0; l < c.L; l++)
+    for (int i = 0; i < n;) {
+      int j = i + 1;
+      while (j < n && mbs[j] == mbs[j - 1] + 1) j++;
+      const int acc = (accumulate || i > 0) ? 1 : 0, nrows = (j - i) * st->y.gain_rows;
+      if (c.attn) TBP_HIP(tbp::gain_partials_sum(st->gain_part(l, 0, mbs[i]), nrows, c.d, acc, st->dg1[l], s));
+      TBP_HIP(tbp::gain_partials_sum(st->gain_part(l, 1, mbs[i]), nrows, c.d, acc, st->dg2[l], s));
+      i = j;
+    }
   return TBP_OK;
 }
 
@@ -758,6 +766,29 @@ tbp_status tbp_rmsnorm_fwd(int dtype, int rows, int d, float eps, const void* x,
 }
 
 size_t tbp_rmsnorm_p1_scratch_bytes(int d) { return d > 0 ? (size_t)tbp::kNormPartialBlocks * d * sizeof(float) : 0; }
+
+int tbp_rmsnorm_partial_rows(int dtype, int rows, int d) {
+  if ((dtype != TBP_F32 && dtype != TBP_BF16) || d < 1 || d > tbp::max_d_model(dtype)) return 0;
+  return tbp::rmsnorm_partial_rows(dtype, rows, d);
+}
+
+tbp_status tbp_rmsnorm_p1_partials(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
+                                   const void* resid, void* dx, float* partials_out, void* stream) {
+  if (check_dtype(dtype) != TBP_OK) return TBP_EINVAL;
+  if (rows < 0 || d < 1 || d % vecq(dtype) || d > tbp::max_d_model(dtype)) return fail(TBP_EINVAL, "bad rows / d");
+  if (rows == 0) return TBP_OK;
+  if (!g || !partials_out || !dy || !x || !dx) return fail(TBP_EINVAL, "null pointer");
+  TBP_HIP(tbp::rmsnorm_p1_rows(dtype, rows, d, eps, dy, x, g, resid, dx, partials_out, static_cast<hipStream_t>(stream)));
+  return TBP_OK;
+}
+
+tbp_status tbp_gain_partials_sum(const float* partials, int n_rows, int d, int accumulate, float* dg_out, void* stream) {
+  if (n_rows < 0 || d < 1) return fail(TBP_EINVAL, "bad n_rows / d");
+  if (!dg_out || (n_rows > 0 && !partials)) return fail(TBP_EINVAL, "null pointer");
+  if (n_rows == 0 && accumulate) return TBP_OK;
+  TBP_HIP(tbp::gain_partials_sum(partials, n_rows, d, accumulate ? 1 : 0, dg_out, static_cast<hipStream_t>(stream)));
+  return TBP_OK;
+}
 
 tbp_status tbp_rmsnorm_p1(int dtype, int rows, int d, float eps, const void* dy, const void* x, const void* g,
                           const void* resid, void* dx, float* dg_out, void* scratch, void* stream) {

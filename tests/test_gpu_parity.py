@@ -140,6 +140,38 @@ def test_rmsnorm_fwd_and_p1(dtype, rows, d):
     assert max_rel(to_np(dx2), ops.rmsnorm_p1(dy64, x64, g64, eps)) < out_tol
 
 
+@pytest.mark.parametrize("dtype,rows,d", [("bf16", 4096, 4096), ("bf16", 2051, 5120), ("bf16", 515, 8192), ("bf16", 300, 2048),
+                                          ("bf16", 3, 264), ("f32", 130, 1028)])
+def test_rmsnorm_p1_partial_rows_and_their_sum(dtype, rows, d):
+    """The two halves of the RMSNorm backward as the stage runs them: backward-p1 leaves dx and the partial rows of the
+    gain gradient, backward-p2 adds partial rows up; partial rows of two micro-batches stored one after the other are
+    summed by one call."""
+    _say(f"rmsnorm partial rows dtype={dtype} rows={rows} d={d}")
+    eps = 1e-6
+    x, dy, res, x2, dy2 = (_rnd(31, n, (rows, d), dtype) for n in ("x", "dy", "res", "x2", "dy2"))
+    g = si.store_round(1.0 + 0.1 * si.standard_normal(31, "g", (d,)), dtype)
+    f64 = lambda a: a.astype(np.float64)
+    out_tol = 4.5e-3 if dtype == "bf16" else 2e-6
+    n_part = tbp.lib().tbp_rmsnorm_partial_rows(tbp.TBP_BF16 if dtype == "bf16" else tbp.TBP_F32, rows, d)
+    assert 1 <= n_part <= min(rows, 256)
+    dx, parts = tbp.tbp_rmsnorm_p1_partials(to_dev(dy, dtype), to_dev(x, dtype), to_dev(g, dtype), eps, resid=to_dev(res, dtype))
+    assert parts.shape == (n_part, d)
+    assert max_rel(to_np(dx), f64(res) + ops.rmsnorm_p1(f64(dy), f64(x), f64(g), eps)) < out_tol
+    want = ops.rmsnorm_p2(f64(dy), f64(x), eps)
+    assert max_rel(to_np(tbp.tbp_gain_partials_sum(parts)), want) < 2e-5
+    dx2, parts2 = tbp.tbp_rmsnorm_p1_partials(to_dev(dy2, dtype), to_dev(x2, dtype), to_dev(g, dtype), eps)
+    assert max_rel(to_np(dx2), ops.rmsnorm_p1(f64(dy2), f64(x2), f64(g), eps)) < out_tol
+    both = torch.cat([parts, parts2], dim=0).contiguous()
+    want2 = ops.rmsnorm_p2(np.concatenate([f64(dy), f64(dy2)]), np.concatenate([f64(x), f64(x2)]), eps)
+    assert max_rel(to_np(tbp.tbp_gain_partials_sum(both)), want2) < 2e-5
+    acc = tbp.tbp_gain_partials_sum(parts)
+    tbp.tbp_gain_partials_sum(parts2, dg=acc)
+    assert max_rel(to_np(acc), want2) < 2e-5
+    # the one-call form agrees bit for bit (same kernels)
+    dx1, dg1 = tbp.tbp_rmsnorm_p1(to_dev(dy, dtype), to_dev(x, dtype), to_dev(g, dtype), eps, resid=to_dev(res, dtype))
+    assert torch.equal(dx1, dx) and torch.equal(dg1, tbp.tbp_gain_partials_sum(parts))
+
+
 @pytest.mark.parametrize("dtype,rows,f", [("bf16", 129, 11008), ("bf16", 7, 5504), ("f32", 130, 688), ("f32", 1, 4)])
 def test_swiglu_fwd_and_p1(dtype, rows, f):
     _say(f"swiglu dtype={dtype} rows={rows} f={f}")

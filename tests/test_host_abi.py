@@ -39,7 +39,11 @@ def test_stash_sizes_follow_the_stash_rule():
             a_el = d + 2 * f
         got = _sizes(s, attention=tbp.TBP_ATTN_MATERIALISED)
         w_expect = L * M * T * w_el * 2
-        assert w_expect <= got["w_stash_bytes"] <= w_expect * 1.001 + L * 2 * M * d * 4 + 4096 * L
+        # + per norm and micro-batch the fp32 partial rows of the gain gradient, as backward-p1's row kernel leaves them
+        n_part = tbp.lib().tbp_rmsnorm_partial_rows(tbp.TBP_BF16, T, d)
+        assert 1 <= n_part <= 256
+        g_expect = L * 2 * M * n_part * d * 4          # (room for both norms of a layer, used or not)
+        assert w_expect + g_expect <= got["w_stash_bytes"] <= w_expect * 1.001 + g_expect + 4096 * L
         assert got["a_stash_bytes"] == L * M * T * a_el * 2
         assert got["arena_bytes"] >= got["w_stash_bytes"] + got["a_stash_bytes"] + got["workspace_bytes"]
         if s.n_heads:     # fused attention keeps a row log-sum-exp (fp32 per token and head) instead of the probabilities
@@ -150,6 +154,11 @@ def test_single_op_argument_checks():
     assert L.tbp_softmax_fwd(1, 1, 8192, 1, fake, fake, None) == 1
     assert L.tbp_rope(1, 4, 8, 2, 24, 48, fake, 0, fake, None) == 1
     assert L.tbp_rmsnorm_p1_scratch_bytes(4096) == 256 * 4096 * 4
+    # partial rows of the gain gradient: one per workgroup of the row kernel, never more than 256, none without rows
+    assert L.tbp_rmsnorm_partial_rows(1, 4096, 4096) == 256 and L.tbp_rmsnorm_partial_rows(1, 0, 4096) == 0
+    assert 1 <= L.tbp_rmsnorm_partial_rows(1, 5, 264) <= 5 and 1 <= L.tbp_rmsnorm_partial_rows(0, 37, 256) <= 37
+    assert L.tbp_rmsnorm_p1_partials(1, 4, 12, 1e-6, fake, fake, fake, None, fake, fake, None) == 1
+    assert L.tbp_gain_partials_sum(None, 3, 64, 0, fake, None) == 1
     # the variant with the library's static scratch refuses widths its array was not built for, before any device call
     assert L.tbp_rmsnorm_p1_static(1, 4, 8200, 1e-6, fake, fake, fake, None, fake, fake, None) == 1
     assert b"static scratch" in L.tbp_last_error()

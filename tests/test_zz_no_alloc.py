@@ -33,10 +33,11 @@ def _case(L, dtype, rows, d, seed, use_resid):
     ws = torch.empty(L.tbp_rmsnorm_p1_scratch_bytes(d), dtype=torch.uint8, device=DEV)
     stream = torch.cuda.current_stream().cuda_stream
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
+    n_allocs = lambda: torch.cuda.memory_stats().get("allocation.all.allocated", 0)      # cumulative count: only ever grows
+    before = n_allocs()
     assert L.tbp_rmsnorm_p1_static(code, rows, d, eps, p(dy_), p(dx_), p(dg_), rp, p(out_new), p(dg_new), stream) == 0, \
         L.tbp_last_error()
-    assert torch.cuda.memory_allocated() == before
+    assert n_allocs() == before
     assert L.tbp_rmsnorm_p1(code, rows, d, eps, p(dy_), p(dx_), p(dg_), rp, p(out_ref), p(dg_ref), p(ws), stream) == 0, \
         L.tbp_last_error()
     torch.cuda.synchronize()
