@@ -51,7 +51,7 @@ def main() -> int:
     ap.add_argument("--gain-grad", choices=["partials", "literal"], default="partials",
                     help="RMSNorm gain gradients: fp32 partials left by p1 and summed in p2 (default), or computed in p2 "
                          "from stashed norm inputs and output derivatives")
-    ap.add_argument("--attention", choices=["auto", "materialised", "fused"], default="auto",
+    ap.add_argument("--attention", choices=["auto", "materialised", "fused", "fused-recompute"], default="auto",
                     help="attention of each layer: fused kernels keeping only a row log-sum-exp (the default where built) "
                          "or separate products with the probabilities stashed")
     ap.add_argument("--no-cpu-baseline", action="store_true",
@@ -66,6 +66,9 @@ def main() -> int:
                     help="skip the extra passes that time other call orders (p2 interleaved with p1, partial flushes)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the short runs of the other benchmark configurations")
+    ap.add_argument("--probe-kernels", action="store_true",
+                    help="for hardware-counter runs: the plain 1 GiB device copies (calibration) and a few launches of each "
+                         "HBM-bound backward-p1 kernel (and the fused attention backward) at this workload's shapes")
     ap.add_argument("--probe", action="store_true",
                     help="for hardware-counter runs: one forward/p1 pass, then a plain 1 GiB device copy (calibration) "
                          "and two K-concatenated p2 passes; prints nothing but a marker line")
@@ -85,6 +88,10 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    if args.probe_kernels:
+        rates = kernel_rates(shape, tbp, torch, dev, tdt, probe=True)
+        print(json.dumps({"probe_kernels": shape.name, "copy_bytes": 1 << 30, "rates": rates}))
+        return 0
     gen = torch.Generator(device=dev)
     gen.manual_seed(shape.seed)
 
@@ -100,7 +107,8 @@ def main() -> int:
                        "g1": [randn(d, std=0.02, mean=1.0) for _ in range(L)]})
     xs = [randn(shape.tokens, d) for _ in range(M)]
     dys = [randn(shape.tokens, d) for _ in range(M)]
-    attn = {"auto": tbp.TBP_ATTN_AUTO, "materialised": tbp.TBP_ATTN_MATERIALISED, "fused": tbp.TBP_ATTN_FUSED}[args.attention]
+    attn = {"auto": tbp.TBP_ATTN_AUTO, "materialised": tbp.TBP_ATTN_MATERIALISED, "fused": tbp.TBP_ATTN_FUSED,
+            "fused-recompute": tbp.TBP_ATTN_FUSED_RECOMPUTE}[args.attention]
     gain = tbp.TBP_GAIN_LITERAL if args.gain_grad == "literal" else tbp.TBP_GAIN_PARTIALS
     st = tbp.Stage(tbp.config_from_shape(shape, attention=attn, gain_grad=gain), params, dev)
     x_out = torch.empty_like(xs[0])
@@ -176,7 +184,8 @@ def main() -> int:
                    "head_dim": shape.head_dim, "d_ffn": f, "seq": shape.seq, "micro_batch": shape.micro_batch,
                    "n_microbatches": M, "p2_mode": "k-concatenated, deferred until all p1 done",
                    "attention": ("none" if not shape.n_heads else "materialised" if args.attention == "materialised" else
-                                 "fused" if shape.dtype == "bf16" and shape.head_dim in (64, 128) else "materialised"),
+                                 "materialised" if not (shape.dtype == "bf16" and shape.head_dim in (64, 128)) else
+                                 "fused, dq by recompute pass" if args.attention == "fused-recompute" else "fused"),
                    "gain_grad": args.gain_grad},
         "pct_of_bf16_mfma_peak": round(100.0 * p2_tflops / PEAK_BF16_TFLOPS, 2),
         "p2_ms": round(statistics.median(p2_ms), 3),
@@ -403,7 +412,7 @@ def graph_replay(st, tbp, torch, xs, dys, x_out, dx_out, M, reps) -> dict:
             "p2_ms": round(statistics.median(ms[2]), 3)}
 
 
-def kernel_rates(shape, tbp, torch, dev, tdt) -> dict:
+def kernel_rates(shape, tbp, torch, dev, tdt, probe=False) -> dict:
     """Achieved HBM rate (algorithmic bytes / kernel time) of the elementwise backward-p1 kernels at this
     workload's per-micro-batch shapes, each timed alone with events over back-to-back launches."""
     T, d, f, S, H, B = shape.tokens, shape.d_model, shape.d_ffn, shape.seq, shape.n_heads, shape.micro_batch
@@ -411,7 +420,7 @@ def kernel_rates(shape, tbp, torch, dev, tdt) -> dict:
     rn = lambda *s: torch.randn(*s, device=dev, dtype=torch.float32).to(tdt)
     res = {}
 
-    def timeit(make_fn, nbytes, name, reps=24):
+    def timeit(make_fn, nbytes, name, reps=8 if probe else 24):
         """make_fn(i) -> launcher over the i-th private buffer set; enough sets are rotated that their total size
         exceeds the 256 MB on-package cache several times, so the rate is an HBM rate, not a cache rate."""
         nset = max(2, min(8, int(1.5e9 // max(nbytes, 1)) + 1))
@@ -444,7 +453,7 @@ def kernel_rates(shape, tbp, torch, dev, tdt) -> dict:
                                     "what": "torch copy_ of 1 GiB (read + write counted)"}
     del src, dst
     sink = torch.empty(1024 * 256, device=dev, dtype=torch.float32)
-    blocks, iters = 1024, 4096
+    blocks, iters = 1024, (64 if probe else 4096)
 
     def mfma_loop(seed):
         L.tbp_mfma_ceiling(blocks, 64, seed.data_ptr(), sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
@@ -461,7 +470,7 @@ def kernel_rates(shape, tbp, torch, dev, tdt) -> dict:
                                   "TFLOP/s_zero_operands": mfma_loop(torch.zeros(4096, device=dev, dtype=torch.bfloat16)),
                                   "what": "register-resident 32x32x16 bf16 MFMA loop, 4 waves per CU, ~7 ms; "
                                           "N(0,1) operands (the figure used) and all-zero operands"}
-    if shape.dtype == "bf16":
+    if shape.dtype == "bf16" and not probe:
         # the vendor library's product of the same shape and operand layout as the largest dW (context, not a target:
         # torch.matmul on X^T [d, K] and dY [K, 2f], bf16 result), next to this library's kernel under the same
         # power state, both on N(0,1) operands

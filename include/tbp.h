@@ -24,7 +24,17 @@
  *     graph runs, so record sequences that a replay may repeat as they are (a whole step returns every
  *     micro-batch to EMPTY).
  *   - Argument errors are detected on the host before anything is launched (TBP_EINVAL /
- *     TBP_ESTATE / TBP_ENOMEM): a failing call launches nothing and changes no state.
+ *     TBP_ESTATE / TBP_ENOMEM): such a call launches nothing and changes no state.  A launch that HIP
+ *     refuses in the middle of a call (TBP_EDEVICE) is different: the kernels enqueued before it still
+ *     run, the micro-batch's state does not advance, and what the call was writing (its stash rows,
+ *     workspace, outputs) is undefined; reset the stage (tbp_stage_reset) or repeat the call.
+ *   - Streams.  A stage has ONE workspace (temporaries of a call, the rotation table, scratch of split
+ *     products) and recycles activation slots and stash rows on the host when a call is enqueued.  Forward
+ *     and backward-p1 calls of a stage must therefore be ordered with respect to each other on the device
+ *     (same stream, or events), and so must any two calls that touch the same micro-batch index or
+ *     activation slot.  backward-p2 shares no workspace with them: a p2 call may run on another stream concurrently
+ *     with forward / p1 calls of OTHER micro-batches, provided it is ordered after the p1 calls of its own
+ *     set and before any forward that reuses those micro-batch indices; two p2 calls must not overlap each other.
  *   - Layouts: activations and gradients are token-major, row-major [tokens, width] with
  *     tokens = micro_batch * seq and sequence b in rows b*seq .. (b+1)*seq-1.  Weights are
  *     row-major [in, out] so that Y = X W, dX = dY W^T, dW = X^T dY.  q/k/v projections are one
@@ -71,8 +81,12 @@ typedef enum { TBP_P2_LOOP = 0, TBP_P2_KCONCAT = 1 } tbp_p2_mode;
  *   FUSED         one forward kernel and one backward kernel that never write scores or probabilities: only the
  *                 row log-sum-exp [batch, heads, seq] is stashed and p1 rebuilds the probabilities from it
  *                 (bf16 storage, head_dim 64 or 128; TBP_EINVAL otherwise);
+ *   FUSED_RECOMPUTE  FUSED, with a backward whose dq comes from a second pass over the keys that rebuilds the scores
+ *                 and dP instead of from a product with dS^T written out by the first pass: three more products
+ *                 per tile, no dS^T workspace (batch * heads * seq^2 storage-type elements less per stage), the same
+ *                 speed within 1 % at the benchmark shapes; same availability rule as FUSED;
  *   AUTO          FUSED where it is available, MATERIALISED elsewhere. */
-typedef enum { TBP_ATTN_AUTO = 0, TBP_ATTN_MATERIALISED = 1, TBP_ATTN_FUSED = 2 } tbp_attention;
+typedef enum { TBP_ATTN_AUTO = 0, TBP_ATTN_MATERIALISED = 1, TBP_ATTN_FUSED = 2, TBP_ATTN_FUSED_RECOMPUTE = 3 } tbp_attention;
 
 /* Where the gradient of an RMSNorm gain, dg = sum over tokens of dy * x * rsqrt(mean(x^2) + eps), is computed.  A gain
  * is a parameter, so by Section 3.1 its gradient is backward-p2 work; the two settings give the same result:
@@ -251,8 +265,14 @@ tbp_status tbp_attention_fwd(int dtype, int batch, int n_heads, int seq, int hea
 /* Backward-p1 of the fused attention: dq, dk, dv (not yet rotated back) into the q | k | v column blocks of dqkv
  * [batch*seq, ld_dqkv], from qkv, the forward's out and lse, and d_out = derivative of out (out and d_out dense:
  * ld_out == n_heads*head_dim).  The probabilities are rebuilt from lse; dS = P * (dP - rowsum(d_out * out)).
- * scratch: device, 256-byte aligned, >= tbp_attention_p1_scratch_bytes(batch, n_heads, seq) (row sums and dS^T). */
+ * scratch: device, 256-byte aligned, >= tbp_attention_p1_scratch_bytes(batch, n_heads, seq) (row sums and dS^T).
+ * tbp_attention_p1_recompute is the same operation with dq from a recompute pass (see TBP_ATTN_FUSED_RECOMPUTE): its
+ * scratch holds the row sums only, tbp_attention_p1_recompute_scratch_bytes(batch, n_heads, seq) bytes. */
 size_t tbp_attention_p1_scratch_bytes(int batch, int n_heads, int seq);
+size_t tbp_attention_p1_recompute_scratch_bytes(int batch, int n_heads, int seq);
+tbp_status tbp_attention_p1_recompute(int dtype, int batch, int n_heads, int seq, int head_dim, int causal,
+                                      const void* qkv, int ld_qkv, const void* out, const void* d_out, int ld_out,
+                                      const float* lse, void* dqkv, int ld_dqkv, void* scratch, void* stream);
 tbp_status tbp_attention_p1(int dtype, int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv,
                             int ld_qkv, const void* out, const void* d_out, int ld_out, const float* lse, void* dqkv,
                             int ld_dqkv, void* scratch, void* stream);

@@ -11,7 +11,7 @@ import os
 import torch
 
 __all__ = [
-    "TBP_F32", "TBP_BF16", "TBP_P2_LOOP", "TBP_P2_KCONCAT", "TBP_ATTN_AUTO", "TBP_ATTN_MATERIALISED", "TBP_ATTN_FUSED", "TBP_GAIN_PARTIALS", "TBP_GAIN_LITERAL", "NN", "NT", "TN", "TbpError", "lib", "library_path",
+    "TBP_F32", "TBP_BF16", "TBP_P2_LOOP", "TBP_P2_KCONCAT", "TBP_ATTN_AUTO", "TBP_ATTN_MATERIALISED", "TBP_ATTN_FUSED", "TBP_ATTN_FUSED_RECOMPUTE", "TBP_GAIN_PARTIALS", "TBP_GAIN_LITERAL", "NN", "NT", "TN", "TbpError", "lib", "library_path",
     "tbp_config", "tbp_stash_query", "Stage", "tbp_gemm", "tbp_rmsnorm_fwd", "tbp_rmsnorm_p1", "tbp_rmsnorm_p1_partials", "tbp_gain_partials_sum", "tbp_rmsnorm_p1_static", "tbp_rmsnorm_gain_p2", "tbp_swiglu_fwd",
     "tbp_swiglu_p1", "tbp_rope_table", "tbp_rope", "tbp_softmax_fwd", "tbp_softmax_p1", "tbp_version",
     "tbp_attention_fwd", "tbp_attention_p1",
@@ -20,7 +20,7 @@ __all__ = [
 
 TBP_F32, TBP_BF16 = 0, 1
 TBP_P2_LOOP, TBP_P2_KCONCAT = 0, 1
-TBP_ATTN_AUTO, TBP_ATTN_MATERIALISED, TBP_ATTN_FUSED = 0, 1, 2
+TBP_ATTN_AUTO, TBP_ATTN_MATERIALISED, TBP_ATTN_FUSED, TBP_ATTN_FUSED_RECOMPUTE = 0, 1, 2, 3
 TBP_GAIN_PARTIALS, TBP_GAIN_LITERAL = 0, 1
 NN, NT, TN = 0, 1, 2
 _STATUS = {0: "TBP_OK", 1: "TBP_EINVAL", 2: "TBP_ESTATE", 3: "TBP_ENOMEM", 4: "TBP_EDEVICE"}
@@ -103,6 +103,9 @@ def lib() -> C.CDLL:
         L.tbp_attention_p1_scratch_bytes.argtypes = [C.c_int] * 3
         L.tbp_attention_p1_scratch_bytes.restype = C.c_size_t
         L.tbp_attention_p1.argtypes = [C.c_int] * 6 + [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        L.tbp_attention_p1_recompute.argtypes = L.tbp_attention_p1.argtypes
+        L.tbp_attention_p1_recompute_scratch_bytes.argtypes = [C.c_int] * 3
+        L.tbp_attention_p1_recompute_scratch_bytes.restype = C.c_size_t
         L.tbp_attention_fwd.argtypes = [C.c_int] * 6 + [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.tbp_rmsnorm_p1_scratch_bytes.argtypes = [C.c_int]
         L.tbp_rmsnorm_gain_p2.argtypes = [C.c_int, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 3
@@ -369,15 +372,16 @@ def tbp_attention_fwd(qkv, seq, n_heads, head_dim, causal=True):
     return out, lse
 
 
-def tbp_attention_p1(qkv, out, d_out, lse, seq, n_heads, head_dim, causal=True):
-    """-> dqkv [batch*seq, 3*n_heads*head_dim] (dq | dk | dv, not rotated back)."""
+def tbp_attention_p1(qkv, out, d_out, lse, seq, n_heads, head_dim, causal=True, recompute=False):
+    """-> dqkv [batch*seq, 3*n_heads*head_dim] (dq | dk | dv, not rotated back).  recompute: tbp_attention_p1_recompute."""
     rows = qkv.shape[0]
     batch = rows // seq
     dqkv = torch.empty_like(qkv)
-    nbytes = lib().tbp_attention_p1_scratch_bytes(batch, n_heads, seq)
+    L = lib()
+    nbytes = (L.tbp_attention_p1_recompute_scratch_bytes if recompute else L.tbp_attention_p1_scratch_bytes)(batch, n_heads, seq)
     scratch = torch.empty(nbytes + 256, dtype=torch.uint8, device=qkv.device)
     base = (scratch.data_ptr() + 255) // 256 * 256
-    _check(lib().tbp_attention_p1(_dt(qkv), batch, n_heads, seq, head_dim, 1 if causal else 0, _ptr(qkv), qkv.stride(0),
+    _check((L.tbp_attention_p1_recompute if recompute else L.tbp_attention_p1)(_dt(qkv), batch, n_heads, seq, head_dim, 1 if causal else 0, _ptr(qkv), qkv.stride(0),
                                   _ptr(out), _ptr(d_out), out.stride(0), _ptr(lse), _ptr(dqkv), dqkv.stride(0), base,
                                   _stream()))
     return dqkv

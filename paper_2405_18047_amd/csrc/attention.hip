@@ -304,7 +304,7 @@ struct AttnBwdParams {
 // of its neighbours.  One workgroup barrier per 32-query tile; the hand-over buffers and the query-step images are
 // double / triple buffered so that neither side ever waits for the other beyond that barrier.  The right waves also
 // issue all asynchronous copies (they have no other vector-memory operations, so their copy counter is exact).
-template <int DH>
+template <int DH, bool WRITE_DST>
 __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p) {
   using HT = HeadTile<DH>;
   constexpr int KS = DH / 16, DT = DH / 32, BQ = 64;
@@ -416,10 +416,12 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
         // (tracked, their acknowledgements cost a quarter of the kernel's time).
         const u32x4 s0 = __builtin_bit_cast(u32x4, ks[0]), s1 = __builtin_bit_cast(u32x4, ks[1]);
         const u32x2 dsv[4] = {u32x2{s0[0], s0[1]}, u32x2{s0[2], s0[3]}, u32x2{s1[0], s1[1]}, u32x2{s1[2], s1[3]}};
+        if constexpr (WRITE_DST) {
 #pragma unroll
-        for (int e4 = 0; e4 < 4; e4++) *reinterpret_cast<LDS_AS u32x2*>(stg_wr + 64 * (tile & 1) + 16 * e4) = dsv[e4];
+          for (int e4 = 0; e4 < 4; e4++) *reinterpret_cast<LDS_AS u32x2*>(stg_wr + 64 * (tile & 1) + 16 * e4) = dsv[e4];
+        }
         // (LDS operations of a wave execute in order: the reads below see the writes above and those of the tile before)
-        if (tile & 1) {
+        if (WRITE_DST && (tile & 1)) {
           const int qe = qt0 - 32;                              // first query of the step; the step lies inside one panel
           const long pan = ((long)(qe / kPanel) * p.S * kPanel + qe % kPanel) * 2;
 #pragma unroll
@@ -579,6 +581,176 @@ __global__ __launch_bounds__(512) void attn_bwd_kv_split_kernel(AttnBwdParams p)
   }
 }
 
+// ------------------------------------------------------------------------------------------ backward-p1: dQ
+// dQ = scale * dS K is a contraction over keys.  This pass is oriented like the forward (S^T = K Q^T: a lane owns one
+// query, so lse and delta of the row are per-lane scalars): per block of 64 keys it recomputes S^T and dP^T = V dO^T,
+// forms P^T = exp2(S^T c - lse) and dS^T = P^T (dP^T - delta) in the accumulators and feeds dS^T straight into
+// dQ^T += K^T dS^T (the B-operand trick of the file header), accumulating dQ^T in registers over all key blocks.
+// Three products per tile instead of one, but no dS^T is written to or read from memory, nothing is added
+// atomically, and the result is bit-reproducible.  Workgroup = 4 waves x 32 queries, K and V blocks double-buffered
+// through LDS exactly as in the forward.
+struct AttnDqParams {
+  const bf16_t* qkv; long ld_qkv;
+  const bf16_t* dout; long ld_do;
+  const float* lse;                    // [B, H, S]
+  const float* delta;                  // [B*S, H]
+  bf16_t* dqkv; long ld_dqkv;          // dq block is written (columns h * DH ..)
+  int B, H, S, causal;
+  float scale, scale_log2e;
+};
+
+template <int DH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(AttnDqParams p) {
+  using HT = HeadTile<DH>;
+  constexpr int KS = DH / 16, DT = DH / 32, BKV = 64;
+  constexpr int IMG = BKV * HT::RB, SLOT = 2 * IMG;
+  constexpr int NCH = IMG / 1024 / 4;
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  lds_u8* const lds = LDS_PTR(unsigned char, smem_raw);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+
+  const int lane = threadIdx.x & 63, ql = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qb = (int)gridDim.y - 1 - (int)blockIdx.y;             // longest (last) query blocks first
+  const int h = (int)blockIdx.x % p.H, b = (int)blockIdx.x / p.H;
+  const int q0 = qb * 128, qw0 = q0 + 32 * wave, query = qw0 + ql;
+  const int d = p.H * DH;
+  const long tok0 = (long)b * p.S;
+  const long bh = (long)b * p.H + h;
+
+  const typename HT::Offsets fo = HT::offsets(lane);
+  // ---- the block's 128 query rows into the second slot and their output derivatives into the first (coalesced copies)
+  {
+    const u32x4 dq = make_desc(p.qkv + (tok0 + q0) * p.ld_qkv + h * DH, (uint32_t)((long)(p.S - q0) * p.ld_qkv * 2));
+    const u32x4 dd = make_desc(p.dout + (tok0 + q0) * p.ld_do + h * DH, (uint32_t)((long)(p.S - q0) * p.ld_do * 2));
+#pragma unroll
+    for (int i = 0; i < 2 * NCH; i++) {
+      int row; unsigned go, gd;
+      HT::plan(wave + 4 * i, lane, p.ld_qkv, row, go);
+      HT::plan(wave + 4 * i, lane, p.ld_do, row, gd);
+      const bool ok = q0 + row < p.S;
+      dma16(lds0 + SLOT + (wave + 4 * i) * 1024, dq, ok ? go : kOob);
+      dma16(lds0 + (wave + 4 * i) * 1024, dd, ok ? gd : kOob);
+    }
+  }
+  int c_row[NCH];
+  unsigned c_off[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; i++) HT::plan(wave + 4 * i, lane, p.ld_qkv, c_row[i], c_off[i]);
+  const int kv_end = p.causal ? (q0 + 128 < p.S ? q0 + 128 : p.S) : p.S;
+  const int nblk = (kv_end + BKV - 1) / BKV;
+  auto issue = [&](int j) {
+    const int kv0 = j * BKV;
+    const bf16_t* kb = p.qkv + (tok0 + kv0) * p.ld_qkv + d + h * DH;
+    const uint32_t bytes = (uint32_t)((long)(p.S - kv0) * p.ld_qkv * 2);
+    const u32x4 dk = make_desc(kb, bytes), dv = make_desc(kb + d, bytes);
+    const uint32_t base = lds0 + (j & 1) * SLOT + wave * 1024;
+#pragma unroll
+    for (int i = 0; i < NCH; i++) {
+      const unsigned off = (kv0 + c_row[i] < p.S) ? c_off[i] : kOob;
+      dma16(base + i * 4096, dk, off);
+      dma16(base + IMG + i * 4096, dv, off);
+    }
+  };
+  // the row statistics of this lane's query
+  const bool qlive = query < p.S;
+  const float lse_q = qlive ? p.lse[bh * p.S + query] : 0.f;
+  const float dl_q = qlive ? p.delta[(tok0 + query) * p.H + h] : 0.f;
+
+  f32x16 dqt[DT];
+#pragma unroll
+  for (int t = 0; t < DT; t++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) dqt[t][e] = 0.f;
+
+  wait_vmem<0>();
+  __syncthreads();
+  bf16x8 qf[KS], dof[KS];            // this lane's query row and output-derivative row as B operands
+#pragma unroll
+  for (int s = 0; s < KS; s++) {
+    qf[s] = HT::rows_frag(lds + SLOT, fo, 32 * wave, s);
+    dof[s] = HT::rows_frag(lds, fo, 32 * wave, s);
+  }
+  __syncthreads();                   // every wave has its rows: both slots are free for the key blocks
+  issue(0);
+  for (int j = 0; j < nblk; j++) {
+    wait_vmem<0>();
+    __syncthreads();                 // block j has landed; every wave is done with the other slot
+    if (j + 1 < nblk) issue(j + 1);
+    const int kv0 = j * BKV;
+    if (p.causal && kv0 > qw0 + 31) continue;
+    lds_u8* const kimg = lds + (j & 1) * SLOT;
+    lds_u8* const vimg = kimg + IMG;
+    // keys beyond the query (causal) or beyond the sequence do not take part: their probability is zero
+    const bool edge = (p.causal && kv0 + BKV - 1 > qw0) || kv0 + BKV > p.S;
+    const int last = p.causal ? (query < p.S - 1 ? query : p.S - 1) : p.S - 1;
+    const int rel = edge ? last - kv0 - 4 * g : 1 << 20;
+    // one 32-key tile at a time (both tiles at once would need 64 more accumulator registers than a wave has):
+    // S^T and dP^T as two interleaved accumulation chains, fragments one k-step ahead; then dS^T in place and
+    // dQ^T += K^T dS^T over the tile's two k-steps on DT independent accumulators
+#pragma unroll 1
+    for (int kt = 0; kt < 2; kt++) {
+      f32x16 st, dp;
+#pragma unroll
+      for (int e = 0; e < 16; e++) { st[e] = 0.f; dp[e] = 0.f; }
+      bf16x8 kf = HT::rows_frag(kimg, fo, 32 * kt, 0), vf = HT::rows_frag(vimg, fo, 32 * kt, 0);
+#pragma unroll
+      for (int s = 0; s < KS; s++) {
+        bf16x8 nk = kf, nv = vf;
+        if (s + 1 < KS) { nk = HT::rows_frag(kimg, fo, 32 * kt, s + 1); nv = HT::rows_frag(vimg, fo, 32 * kt, s + 1); }
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], st, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[s], dp, 0, 0, 0);
+        kf = nk; vf = nv;
+      }
+      bf16x8 ktf[DT];
+#pragma unroll
+      for (int t = 0; t < DT; t++) ktf[t] = HT::cols_frag(kimg, fo, 32 * kt, 0, t);
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(st[e], p.scale_log2e, -lse_q));
+        pe = (32 * kt + 8 * (e >> 2) + (e & 3) > rel) ? 0.f : pe;
+        st[e] = pe * (dp[e] - dl_q);                         // dS^T
+      }
+#pragma unroll
+      for (int u = 0; u < 2; u++) {
+        const bf16x8 sb = pack8(st, u);
+#pragma unroll
+        for (int t = 0; t < DT; t++) {
+          dqt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf[t], sb, dqt[t], 0, 0, 0);
+          if (u == 0) ktf[t] = HT::cols_frag(kimg, fo, 32 * kt, 1, t);     // the second k-step's fragment, behind the MFMA that used the first
+        }
+      }
+    }
+  }
+
+  // ---- dq = scale * dQ^T, transposed back through LDS and written as whole rows (as the forward writes its output)
+  __syncthreads();
+  constexpr int EROW = DH * 2 + 16;
+  static_assert(128 * EROW <= 2 * SLOT, "the output tile must fit in the ring");
+  lds_u8* const erow = lds + 32 * wave * EROW;
+#pragma unroll
+  for (int t = 0; t < DT; t++)
+#pragma unroll
+    for (int e4 = 0; e4 < 4; e4++) {
+      bf16x4 v;
+#pragma unroll
+      for (int r = 0; r < 4; r++) v[r] = (bf16_t)(dqt[t][4 * e4 + r] * p.scale);
+      *reinterpret_cast<LDS_AS bf16x4*>(erow + ql * EROW + (32 * t + 8 * e4 + 4 * g) * 2) = v;
+    }
+  {  // (LDS operations of a wave execute in order: the reads below see this wave's own writes above)
+    constexpr int LPR = DH / 8, RPI = 64 / LPR;
+    const int rl = lane / LPR, piece = lane % LPR;
+#pragma unroll
+    for (int r0 = 0; r0 < 32; r0 += RPI) {
+      const int qrow = qw0 + r0 + rl;
+      if (qrow < p.S)
+        *reinterpret_cast<u32x4*>(p.dqkv + (tok0 + qrow) * p.ld_dqkv + h * DH + 8 * piece) =
+            *reinterpret_cast<const LDS_AS u32x4*>(erow + (r0 + rl) * EROW + 16 * piece);
+    }
+  }
+}
+
 template <int DH>
 static hipError_t launch_fwd(const AttnParams& p, hipStream_t s) {
   constexpr size_t smem = 2 * 2 * 64 * DH * 2;
@@ -602,9 +774,19 @@ hipError_t attention_fwd(int batch, int n_heads, int seq, int head_dim, int caus
 }
 
 template <int DH>
+static hipError_t launch_bwd_dq(const AttnDqParams& p, hipStream_t s) {
+  constexpr size_t smem = 2 * 2 * 64 * DH * 2;
+  auto kern = attn_bwd_dq_kernel<DH>;
+  static AttrOnce once;
+  if (hipError_t e = once.set(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(p.H * p.B), (unsigned)((p.S + 127) / 128)), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
+template <int DH, bool WRITE_DST>
 static hipError_t launch_bwd_kv_split(const AttnBwdParams& p, hipStream_t s) {
   constexpr size_t smem = 3 * (2 * 64 * DH * 2 + 1024) + 2 * 4 * 4096 + 4 * 32 * 144;     // three slots, two hand-over buffers, dS^T staging
-  auto kern = attn_bwd_kv_split_kernel<DH>;
+  auto kern = attn_bwd_kv_split_kernel<DH, WRITE_DST>;
   static AttrOnce once;
   if (hipError_t e = once.set(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(p.H * p.B), (unsigned)((p.S + 127) / 128)), dim3(512), smem, s, p);
@@ -624,8 +806,20 @@ hipError_t attention_p1(int batch, int n_heads, int seq, int head_dim, int causa
   p.B = batch; p.H = n_heads; p.S = seq; p.causal = causal;
   p.scale = 1.f / sqrtf((float)head_dim);
   p.scale_log2e = 1.4426950408889634f * p.scale;
-  if (head_dim == 128) e = launch_bwd_kv_split<128>(p, s);
-  else if (head_dim == 64) e = launch_bwd_kv_split<64>(p, s);
+  if (!ds_t) {
+    // no dS^T buffer: dQ by the recompute pass
+    if (head_dim == 128) e = launch_bwd_kv_split<128, false>(p, s);
+    else if (head_dim == 64) e = launch_bwd_kv_split<64, false>(p, s);
+    else return hipErrorInvalidValue;
+    if (e != hipSuccess) return e;
+    AttnDqParams q{};
+    q.qkv = p.qkv; q.ld_qkv = ld_qkv; q.dout = p.dout; q.ld_do = ld_out; q.lse = lse; q.delta = delta;
+    q.dqkv = p.dqkv; q.ld_dqkv = ld_dqkv; q.B = batch; q.H = n_heads; q.S = seq; q.causal = causal;
+    q.scale = p.scale; q.scale_log2e = p.scale_log2e;
+    return head_dim == 128 ? launch_bwd_dq<128>(q, s) : launch_bwd_dq<64>(q, s);
+  }
+  if (head_dim == 128) e = launch_bwd_kv_split<128, true>(p, s);
+  else if (head_dim == 64) e = launch_bwd_kv_split<64, true>(p, s);
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
   // dq = scale * dS k = scale * (dS^T)^T k per (sequence, head): contraction over keys, causal: keys <= query

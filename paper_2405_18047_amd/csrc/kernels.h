@@ -127,7 +127,8 @@ hipError_t attention_fwd(int batch, int n_heads, int seq, int head_dim, int caus
 // Backward-p1 of the same: dq, dk, dv into the column blocks of dqkv from qkv, the forward's output and lse and the
 // output derivative d_out (dense rows: ld_out == n_heads*head_dim).  delta: scratch [batch*seq, n_heads] fp32;
 // ds_t: scratch of batch * n_heads * attn_ds_elems(seq) storage-type elements (receives dS^T in panels of kPanel
-// queries: per (sequence, head) [ceil(seq / kPanel)][seq keys][kPanel queries]).
+// queries: per (sequence, head) [ceil(seq / kPanel)][seq keys][kPanel queries]; dq is then one batched product
+// dS K), or nullptr: dq is computed by a second pass over the keys that rebuilds S and dP (no dS^T anywhere).
 hipError_t attention_p1(int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv, long ld_qkv,
                         const void* out, const void* d_out, long ld_out, const float* lse, void* dqkv, long ld_dqkv,
                         float* delta, void* ds_t, hipStream_t s);

@@ -47,6 +47,7 @@ struct Dims {
   size_t e;       // bytes per stored element
   bool attn;
   bool fused;     // attention without stored probabilities (row log-sum-exp only)
+  bool dq_recompute;   // fused attention backward without a dS^T buffer: dq by a recompute pass
   bool literal;   // RMSNorm gain gradients computed in p2 from stashed (x, dy) instead of p1's per-micro-batch partials
   float eps, base;
 };
@@ -119,7 +120,7 @@ Layout plan(const Dims& c) {
   y.ws_t_d0 = off; off += align_up((size_t)c.T * c.d * c.e, 256);
   y.ws_t_d1 = off; off += align_up((size_t)c.T * c.d * c.e, 256);
   // fp32 scores, then dS (materialised attention) or dS^T in the storage type (fused)
-  y.ws_scores = off; off += !c.attn ? 0 : align_up(c.fused ? (size_t)c.B * c.H * tbp::attn_ds_elems(c.S) * c.e
+  y.ws_scores = off; off += (!c.attn || c.dq_recompute) ? 0 : align_up(c.fused ? (size_t)c.B * c.H * tbp::attn_ds_elems(c.S) * c.e
                                                            : (size_t)c.B * c.H * c.S * c.S * sizeof(float), 256);
   y.ws_norm_partials_p2 = off; off += c.literal ? align_up((size_t)tbp::kNormPartialBlocks * c.d * sizeof(float), 256) : 0;
   y.ws_rope = off; off += c.attn ? align_up((size_t)c.S * (c.dh / 2) * sizeof(float2), 256) : 0;
@@ -174,12 +175,13 @@ tbp_status check_config(const tbp_config* cfg, Dims* out) {
     if (c.S > tbp::kMaxSeq) return fail(TBP_EINVAL, "seq %d above the limit %d", c.S, tbp::kMaxSeq);
     if (!(c.base > 0.f)) return fail(TBP_EINVAL, "rope_base must be positive");
   }
-  if (cfg->attention < TBP_ATTN_AUTO || cfg->attention > TBP_ATTN_FUSED) return fail(TBP_EINVAL, "attention must be a tbp_attention value");
+  if (cfg->attention < TBP_ATTN_AUTO || cfg->attention > TBP_ATTN_FUSED_RECOMPUTE) return fail(TBP_EINVAL, "attention must be a tbp_attention value");
   {
     const bool can_fuse = c.attn && c.dtype == TBP_BF16 && (c.dh == 64 || c.dh == 128);
-    if (cfg->attention == TBP_ATTN_FUSED && c.attn && !can_fuse)
+    if ((cfg->attention == TBP_ATTN_FUSED || cfg->attention == TBP_ATTN_FUSED_RECOMPUTE) && c.attn && !can_fuse)
       return fail(TBP_EINVAL, "fused attention needs bf16 storage and head_dim 64 or 128");
     c.fused = can_fuse && cfg->attention != TBP_ATTN_MATERIALISED;
+    c.dq_recompute = c.fused && cfg->attention == TBP_ATTN_FUSED_RECOMPUTE;
   }
   if (cfg->gain_grad != TBP_GAIN_PARTIALS && cfg->gain_grad != TBP_GAIN_LITERAL) return fail(TBP_EINVAL, "gain_grad must be a tbp_gain_grad value");
   c.literal = cfg->gain_grad == TBP_GAIN_LITERAL;
@@ -363,7 +365,7 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
       // probabilities rebuilt from the stashed row log-sum-exp; dq, dk, dv straight into the dqkv slab
       TBP_HIP(tbp::attention_p1(c.B, c.H, c.S, c.dh, c.causal, qkv, 3 * d, st->wslab(l, W_A, mb), da, d,
                                 (const float*)st->aslot(l, A_LSE, slot), dqkv, 3 * d, (float*)st->ws(st->y.ws_delta),
-                                dP, s));
+                                c.dq_recompute ? nullptr : dP, s));
     } else {
       // rowsum(dP * P) per (token, head) = rowsum(da * a): no S x S tensor needed for it
       float* delta = (float*)st->ws(st->y.ws_delta);
@@ -726,9 +728,9 @@ size_t tbp_attention_p1_scratch_bytes(int batch, int n_heads, int seq) {
   return align_up((size_t)batch * seq * n_heads * sizeof(float), 256) + (size_t)batch * n_heads * tbp::attn_ds_elems(seq) * 2;
 }
 
-tbp_status tbp_attention_p1(int dtype, int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv,
-                            int ld_qkv, const void* out, const void* d_out, int ld_out, const float* lse, void* dqkv,
-                            int ld_dqkv, void* scratch, void* stream) {
+static tbp_status attention_p1_checked(int dtype, int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv,
+                                       int ld_qkv, const void* out, const void* d_out, int ld_out, const float* lse, void* dqkv,
+                                       int ld_dqkv, void* scratch, int recompute, void* stream) {
   if (dtype != TBP_BF16) return fail(TBP_EINVAL, "fused attention is built for bf16 storage only");
   if (head_dim != 64 && head_dim != 128) return fail(TBP_EINVAL, "fused attention needs head_dim 64 or 128");
   if (batch < 0 || n_heads < 0 || seq < 0) return fail(TBP_EINVAL, "negative size");
@@ -744,10 +746,29 @@ tbp_status tbp_attention_p1(int dtype, int batch, int n_heads, int seq, int head
   if ((uintptr_t)qkv % 16 || (uintptr_t)out % 16 || (uintptr_t)d_out % 16 || (uintptr_t)dqkv % 16 || (uintptr_t)scratch % 256)
     return fail(TBP_EINVAL, "tensors must be 16-byte aligned, scratch 256-byte aligned");
   float* delta = static_cast<float*>(scratch);
-  void* ds_t = static_cast<char*>(scratch) + align_up((size_t)batch * seq * n_heads * sizeof(float), 256);
+  void* ds_t = recompute ? nullptr : static_cast<char*>(scratch) + align_up((size_t)batch * seq * n_heads * sizeof(float), 256);
   TBP_HIP(tbp::attention_p1(batch, n_heads, seq, head_dim, causal ? 1 : 0, qkv, ld_qkv, out, d_out, ld_out, lse, dqkv,
                             ld_dqkv, delta, ds_t, static_cast<hipStream_t>(stream)));
   return TBP_OK;
+}
+
+tbp_status tbp_attention_p1(int dtype, int batch, int n_heads, int seq, int head_dim, int causal, const void* qkv,
+                            int ld_qkv, const void* out, const void* d_out, int ld_out, const float* lse, void* dqkv,
+                            int ld_dqkv, void* scratch, void* stream) {
+  return attention_p1_checked(dtype, batch, n_heads, seq, head_dim, causal, qkv, ld_qkv, out, d_out, ld_out, lse, dqkv,
+                              ld_dqkv, scratch, 0, stream);
+}
+
+size_t tbp_attention_p1_recompute_scratch_bytes(int batch, int n_heads, int seq) {
+  if (batch <= 0 || n_heads <= 0 || seq <= 0) return 0;
+  return align_up((size_t)batch * seq * n_heads * sizeof(float), 256);
+}
+
+tbp_status tbp_attention_p1_recompute(int dtype, int batch, int n_heads, int seq, int head_dim, int causal,
+                                      const void* qkv, int ld_qkv, const void* out, const void* d_out, int ld_out,
+                                      const float* lse, void* dqkv, int ld_dqkv, void* scratch, void* stream) {
+  return attention_p1_checked(dtype, batch, n_heads, seq, head_dim, causal, qkv, ld_qkv, out, d_out, ld_out, lse, dqkv,
+                              ld_dqkv, scratch, 1, stream);
 }
 
 tbp_status tbp_mfma_ceiling(int blocks, int iters, const void* seed, float* sink, void* stream) {

@@ -101,7 +101,7 @@ def test_13b_mlp_block_shape_full_compare():
 def test_stage_with_split_contraction():
     """A stage whose backward-p1 product dh2 = [dg, du] Wgu^T has a small output ([1024, 1024]: 16 large tiles) and a
     very long contraction (2 x 24576): the stage runs it with the contraction split over several workgroups per tile,
-    using scratch from its own workspace, whose arrival counters are cleared once and then reused."""
+    using scratch from its own workspace, whose arrival counters are cleared before every such product."""
     shape = si.StageShape("mlp_long_k", 1, 1024, 0, 0, 24576, 1024, 1, 2, "bf16", 20240525)
     assert tbp.lib().tbp_gemm_workspace_bytes(tbp.TBP_BF16, tbp.NT, shape.tokens, shape.d_model, 2 * shape.d_ffn, 0) > 0
     params, xs, dys = _inputs(shape)

@@ -245,9 +245,11 @@ def test_softmax_fwd_and_p1(dtype, n_mat, seq, causal):
                                                 (1024, 1, 32, 64, True),
                                                 # the longest sequence the kernels take
                                                 (4096, 1, 1, 128, True)])
-def test_fused_attention_backward(seq, nb, H, dh, causal):
-    """dq, dk, dv of the fused backward (probabilities rebuilt from the row log-sum-exp) against the oracle's."""
-    _say(f"attention p1 seq={seq} batch={nb} heads={H} dh={dh} causal={causal}")
+@pytest.mark.parametrize("recompute", [False, True])
+def test_fused_attention_backward(seq, nb, H, dh, causal, recompute):
+    """dq, dk, dv of the fused backward (probabilities rebuilt from the row log-sum-exp) against the oracle's; dq either
+    from the product with the dS^T that the first pass writes out, or from the recompute pass."""
+    _say(f"attention p1 seq={seq} batch={nb} heads={H} dh={dh} causal={causal} recompute={recompute}")
     d = H * dh
     q, k, v, do = (_rnd(42, n, (nb * seq, d), "bf16") for n in ("q", "k", "v", "do"))
     q64, k64, v64 = q.astype(np.float64), k.astype(np.float64), v.astype(np.float64)
@@ -255,7 +257,7 @@ def test_fused_attention_backward(seq, nb, H, dh, causal):
     dq, dk, dv = ops.attention_p1(do.astype(np.float64), q64, k64, v64, P, seq, H, dh)
     qkv = to_dev(np.concatenate([q, k, v], axis=1), "bf16")
     out, lse2 = tbp.tbp_attention_fwd(qkv, seq, H, dh, causal)
-    got = to_np(tbp.tbp_attention_p1(qkv, out, to_dev(do, "bf16"), lse2, seq, H, dh, causal))
+    got = to_np(tbp.tbp_attention_p1(qkv, out, to_dev(do, "bf16"), lse2, seq, H, dh, causal, recompute=recompute))
     for name, ref, blk in (("dq", dq, got[:, :d]), ("dk", dk, got[:, d:2 * d]), ("dv", dv, got[:, 2 * d:])):
         err = max_rel(blk, ref)
         _say(f"   {name}: {err:.2e}")
@@ -343,7 +345,9 @@ SMALL = {
 # the attention of the bf16 stages with head_dim 64 / 128 runs fused by default; the same stages are also run with the
 # materialised form (probabilities stashed)
 STAGE_CASES = [(n, tbp.TBP_ATTN_AUTO) for n in SMALL] + [("small_bf16", tbp.TBP_ATTN_MATERIALISED),
-                                                        ("tiles_bf16", tbp.TBP_ATTN_MATERIALISED)]
+                                                        ("tiles_bf16", tbp.TBP_ATTN_MATERIALISED),
+                                                        ("small_bf16", tbp.TBP_ATTN_FUSED_RECOMPUTE),
+                                                        ("tiles_bf16", tbp.TBP_ATTN_FUSED_RECOMPUTE)]
 
 
 @pytest.mark.parametrize("name,attention", STAGE_CASES)

@@ -51,6 +51,10 @@ def test_stash_sizes_follow_the_stash_rule():
             assert fused["a_stash_bytes"] == L * M * T * ((5 * d + 2 * f) * 2 + s.n_heads * 4)
             assert fused["w_stash_bytes"] == got["w_stash_bytes"]
             assert _sizes(s)["a_stash_bytes"] == fused["a_stash_bytes"]       # AUTO picks it for bf16, head_dim 128
+            # dq by a recompute pass: the same stash, and the dS^T workspace (batch * heads * seq^2 elements) is gone
+            lean = _sizes(s, attention=tbp.TBP_ATTN_FUSED_RECOMPUTE)
+            assert lean["a_stash_bytes"] == fused["a_stash_bytes"] and lean["w_stash_bytes"] == fused["w_stash_bytes"]
+            assert fused["workspace_bytes"] - lean["workspace_bytes"] == s.micro_batch * s.n_heads * s.seq * s.seq * 2
         # gain gradients computed in p2: each norm's input moves from the forward->p1 slots to slabs kept until p2 and
         # the derivative of its output is kept as well; the fp32 partials disappear
         lit = _sizes(s, gain_grad=tbp.TBP_GAIN_LITERAL)
@@ -67,7 +71,7 @@ def test_stash_sizes_follow_the_stash_rule():
 
 
 @pytest.mark.parametrize("field,value", [("d_model", 4100), ("d_ffn", 11004), ("seq", 4104), ("head_dim", 120),
-                                         ("n_layers", 0), ("dtype", 7), ("d_model", 16384), ("seq", 8192), ("attention", 3),
+                                         ("n_layers", 0), ("dtype", 7), ("d_model", 16384), ("seq", 8192), ("attention", 4),
                                          ("gain_grad", 2)])
 def test_bad_configs_are_rejected(field, value):
     cfg = tbp.config_from_shape(si.CONFIGS["llama7b_s1024"])
