@@ -143,10 +143,14 @@ __device__ __forceinline__ bf16x8 read_frag(lds_u8* q) {
 // operands whose contraction index is contiguous in memory: their copies then fetch 128 contiguous bytes per tile
 // row, a whole cache line, where the 32-deep slot fetches every line in two halves one iteration apart and doubles
 // the number of requests to the L2.
-template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD = BK, bool SPLIT = false>
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD = BK, bool SPLIT = false, int RING = 0>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, int tn_i, int z, int split_idx = 0,
                                                int tile_seq = 0) {
-  constexpr int NS = KD == 32 ? STAGES : 2;     // ring slots
+  // RING == 0: the default pipeline of the slot depth (32: ring of STAGES slots; 64: two slots); RING >= 3: the ring
+  // pipeline with that many slots, for either depth
+  constexpr bool RINGPIPE = KD == 32 || RING >= 3;
+  constexpr int NS = RING >= 3 ? RING : (KD == 32 ? STAGES : 2);       // ring slots
+  constexpr int KSTEPS = KD / 16;
   constexpr int WM = BM / 2, WN = BN / 2;       // per-wave tile
   constexpr int TM = WM / 32, TN = WN / 32;     // MFMA tiles per wave
   using TA = OperandTile<BM, AKC, KD>;
@@ -280,7 +284,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  static_assert(BK == 32 && STAGES >= 3, "the 32-deep pipeline is written for two k-steps per slot");
+  static_assert(BK == 32 && (!RINGPIPE || (NS - 2) * L < 64), "the wait counter has 6 bits");
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
   auto first_fragments = [&]() {
 #pragma unroll
@@ -288,24 +292,33 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
 #pragma unroll
     for (int j = 0; j < TN; j++) fb0[j] = read_frag<BN, BKC>(lds + b_base[TB::variant(0, j)] + TB::frag_step(0, j));
   };
-  if constexpr (KD == 32) {
+  if constexpr (RINGPIPE) {
+    // Ring of NS slots, KSTEPS k-steps per slot (an even number: the two fragment register sets alternate).  While
+    // k-step ks - 1 of tile t is multiplied, the fragments of k-step ks are fetched; before the last k-step of a slot
+    // (its fragments are in registers by then) come the wait for tile t + 1 and the workgroup barrier, and during that
+    // last k-step the fragments of (t + 1, k-step 0) are fetched and the copies of tile t + NS - 1 are started.
     if (nk > 0) {
 #pragma unroll
-      for (int t = 0; t < STAGES - 1; t++) {
+      for (int t = 0; t < NS - 1; t++) {
         const CopyJob j = next_job();
 #pragma unroll
         for (int c = 0; c < L; c++) copy_one(j, c);
       }
-      wait_vmem<(STAGES - 2) * L>();          // tile 0 has landed (this wave's share)
+      wait_vmem<(NS - 2) * L>();              // tile 0 has landed (this wave's share)
       __syncthreads();
       first_fragments();
       for (int t = 0; t < nk; t++) {
-        region(fa0, fb0, fa1, fb1, lds + (t % STAGES) * STAGE_BYTES, 1, nullptr);
-        wait_vmem<(STAGES - 3) * L>();        // tile t+1 has landed (this wave's share)
+        lds_u8* const cur = lds + (t % NS) * STAGE_BYTES;
+#pragma unroll
+        for (int ks = 1; ks < KSTEPS; ks++) {
+          if (ks & 1) region(fa0, fb0, fa1, fb1, cur, ks, nullptr);
+          else region(fa1, fb1, fa0, fb0, cur, ks, nullptr);
+        }
+        wait_vmem<(NS - 3) * L>();            // tile t+1 has landed (this wave's share)
         __syncthreads();                      // everyone's share of t+1 landed; everyone is done with tile t-1
-        const CopyJob j = next_job();         // tile t + STAGES - 1
+        const CopyJob j = next_job();         // tile t + NS - 1
         __builtin_amdgcn_sched_barrier(0);
-        region(fa1, fb1, fa0, fb0, lds + ((t + 1) % STAGES) * STAGE_BYTES, 0, &j);
+        region(fa1, fb1, fa0, fb0, lds + ((t + 1) % NS) * STAGE_BYTES, 0, &j);
       }
       wait_vmem<0>();                         // drain the (empty) copies issued past the end
     }
@@ -355,23 +368,31 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
     // clears the counter for the next product and goes on to the epilogue.  Nobody waits for anybody: a workgroup that
     // is not last is simply done.
     // The exchange does not depend on where the workgroups run.  The partial sums are written and read with
-    // device-scope accesses (relaxed atomic stores / loads: they go through to, and come from, the level of the memory
-    // system that all XCDs share, whatever L2 the workgroup sits behind) and the ticket is a device-scope atomic.
+    // device-scope accesses (16-byte buffer stores / loads with the sc1 cache-policy bit: they go through to, and come
+    // from, the level of the memory system that all XCDs share, whatever L2 the workgroup sits behind) and the ticket
+    // is a device-scope atomic.
     // Order: every lane waits until its own stores have completed (vmcnt(0)), the workgroup barrier collects all
     // lanes, only then does lane 0 take the ticket; a workgroup that sees the last ticket therefore follows, in
     // time, the completion of every slice's stores, and its loads cannot be served from a stale cached copy.  No
     // cache-wide write-back or invalidate is involved (such a fence would flush the L2 under every other workgroup's
     // operand panels).  The launch map still puts the slices of a tile on one XCD, but only for speed.
     constexpr long TILE = (long)BM * BN;
+    constexpr int kDeviceScope = 16;        // cache-policy bit "sc1" of the buffer instructions: device scope
     float* const mine = p.split_ws + ((long)tile_seq * p.split + split_idx) * TILE;
+    {
+      const __amdgpu_buffer_rsrc_t rs = make_rsrc(mine, (uint32_t)(TILE * sizeof(float)));
 #pragma unroll
-    for (int i = 0; i < TM; i++)
+      for (int i = 0; i < TM; i++)
 #pragma unroll
-      for (int j = 0; j < TN; j++)
+        for (int j = 0; j < TN; j++)
 #pragma unroll
-        for (int e = 0; e < 16; e++)
-          __hip_atomic_store(mine + ((i * TN + j) * 16 + e) * 256 + tid, acc[i][j][e], __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_AGENT);
+          for (int e4 = 0; e4 < 4; e4++) {
+            u32x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; q++) v[q] = __float_as_uint(acc[i][j][4 * e4 + q]);
+            __builtin_amdgcn_raw_buffer_store_b128(v, rs, ((((i * TN + j) * 4 + e4) * 256 + tid) << 4), 0, kDeviceScope);
+          }
+    }
     wait_vmem<0>();                         // this lane's partial sums have been written
     LDS_AS int* const last_arrival = reinterpret_cast<LDS_AS int*>(lds);     // (the ring is free once all waves are here)
     __syncthreads();
@@ -387,15 +408,17 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
 #pragma unroll
         for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
     for (int sl = 0; sl < p.split; sl++) {
-      const float* const part = p.split_ws + ((long)tile_seq * p.split + sl) * TILE;
+      const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.split_ws + ((long)tile_seq * p.split + sl) * TILE, (uint32_t)(TILE * sizeof(float)));
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int j = 0; j < TN; j++)
 #pragma unroll
-          for (int e = 0; e < 16; e++)
-            acc[i][j][e] += __hip_atomic_load(part + ((i * TN + j) * 16 + e) * 256 + tid, __ATOMIC_RELAXED,
-                                              __HIP_MEMORY_SCOPE_AGENT);
+          for (int e4 = 0; e4 < 4; e4++) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, ((((i * TN + j) * 4 + e4) * 256 + tid) << 4), 0, kDeviceScope);
+#pragma unroll
+            for (int q = 0; q < 4; q++) acc[i][j][4 * e4 + q] += __uint_as_float(v[q]);
+          }
     }
     if (tid == 0) __hip_atomic_store(p.split_cnt + tile_seq, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
@@ -488,7 +511,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
   }
 }
 
-template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD>
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD, int RING = 0>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   int tm_i, tn_i, z = (int)blockIdx.z;
   if (gridDim.z == 1) {
@@ -522,7 +545,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
       tn_i = id / p.tiles_m;
     }
   }
-  gemm_bf16_tile<BM, BN, AKC, BKC, OutT, KD>(p, tm_i, tn_i, z);
+  gemm_bf16_tile<BM, BN, AKC, BKC, OutT, KD, false, RING>(p, tm_i, tn_i, z);
 }
 
 // Batched product with a causal contraction end (rows of tile i contract over (i + 1) * BM indices) and one tile column:
@@ -720,14 +743,14 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
 }
 
 // ------------------------------------------------------------------------------------------ host
-template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD>
+template <int BM, int BN, bool AKC, bool BKC, typename OutT, int KD, int RING = 0>
 static hipError_t launch_bf16(const GemmParams& p0, int batch, hipStream_t s) {
   GemmParams p = p0;
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N + BN - 1) / BN;
-  constexpr size_t smem = (size_t)(KD == 32 ? STAGES : 2) * (BM + BN) * KD * sizeof(bf16_t);
+  constexpr size_t smem = (size_t)(RING >= 3 ? RING : (KD == 32 ? STAGES : 2)) * (BM + BN) * KD * sizeof(bf16_t);
   static_assert(smem <= 160 * 1024, "LDS budget of one gfx950 compute unit");
-  auto kern = gemm_bf16_kernel<BM, BN, AKC, BKC, OutT, KD>;
+  auto kern = gemm_bf16_kernel<BM, BN, AKC, BKC, OutT, KD, RING>;
   static AttrOnce once;
   if (hipError_t e = once.set(reinterpret_cast<const void*>(kern), smem); e != hipSuccess) return e;
   unsigned nt = (unsigned)(p.tiles_m * p.tiles_n);
@@ -824,6 +847,29 @@ static hipError_t launch_bf16_split(const GemmParams& p0, int split, void* ws, i
 #ifndef TBP_TN_DEPTH
 #define TBP_TN_DEPTH 32
 #endif
+#ifndef TBP_SMALL_DEEP_RING
+#define TBP_SMALL_DEEP_RING 4
+#endif
+#ifndef TBP_SMALL_DEEP_KD
+#define TBP_SMALL_DEEP_KD 64
+#endif
+// Small tiles with a deep ring: when the whole output is at most one small tile per compute unit (e.g. [1024, 4096]),
+// no second workgroup shares the CU to cover the first one's waits, and a 32-deep slot of a 128 x 128 tile is
+// multiplied in 256 clocks, so the three slots that a ring of four keeps in flight cover under 800 clocks of memory
+// latency.  Such products get a ring of four 64-deep slots (128 KiB of LDS; one workgroup per CU anyway): three
+// times 512 clocks of cover, and K-contiguous operands are fetched in whole 128-byte lines.  Measured on
+// [1024, 4096] outputs: K = 12288 (NT) 126 -> 107 us, K = 22016 (NT) 237 -> 216 us, K = 11008 (NN) 104 -> 93 us;
+// a ring of eight 32-deep slots gains 3 %, three 64-deep slots lose 5 %, five (all 160 KiB) lose too.
+template <typename OutT>
+static hipError_t dispatch_small_deep(int layout, const GemmParams& p, hipStream_t s) {
+  switch (layout) {
+    case NN: return launch_bf16<128, 128, true, false, OutT, TBP_SMALL_DEEP_KD, TBP_SMALL_DEEP_RING>(p, 1, s);
+    case NT: return launch_bf16<128, 128, true, true, OutT, TBP_SMALL_DEEP_KD, TBP_SMALL_DEEP_RING>(p, 1, s);
+    case TN: return launch_bf16<128, 128, false, false, OutT, 32, 8>(p, 1, s);
+  }
+  return hipErrorInvalidValue;
+}
+
 template <int BM, int BN, typename OutT>
 static hipError_t dispatch_layout(int layout, const GemmParams& p, int batch, hipStream_t s) {
   constexpr int KD = BM >= 256 ? 64 : TBP_KC_DEPTH_SMALL;
@@ -908,6 +954,8 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
                             : launch_bf16_split<256, 256, true, true, bf16_t, 64>(p, plan.split, g.ws, g.ws_counters_zero, s);
   }
   auto run = [&](const GemmParams& q, bool use_big) -> hipError_t {
+    if (!use_big && g.batch == 1 && q.K >= 1024 && (long)((q.M + 127) / 128) * ((q.N + 127) / 128) <= 256)
+      return g.out_f32 ? dispatch_small_deep<float>(g.layout, q, s) : dispatch_small_deep<bf16_t>(g.layout, q, s);
     if (g.out_f32)
       return use_big ? dispatch_layout<256, 256, float>(g.layout, q, g.batch, s)
                      : dispatch_layout<128, 128, float>(g.layout, q, g.batch, s);
