@@ -847,6 +847,10 @@ static hipError_t launch_bf16_split(const GemmParams& p0, int split, void* ws, i
 #ifndef TBP_TN_DEPTH
 #define TBP_TN_DEPTH 32
 #endif
+#ifndef TBP_NARROW_KD
+#define TBP_NARROW_KD 64
+#define TBP_NARROW_RING 0
+#endif
 #ifndef TBP_SMALL_DEEP_RING
 #define TBP_SMALL_DEEP_RING 4
 #endif
@@ -945,8 +949,8 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
   // two or three workgroups share a compute unit and overlap them
   const bool big = g.M >= 256 && g.N >= 256 && tiles_big >= 192 && g.K > 256;
   if (!g.out_f32 && g.batch == 1 && g.causal == CAUSAL_NONE && !g.delta && g.layout != TN && narrow_tiles_pay(g.M, g.N, g.K))
-    return g.layout == NN ? launch_bf16<256, 192, true, false, bf16_t, 64>(p, 1, s)
-                          : launch_bf16<256, 192, true, true, bf16_t, 64>(p, 1, s);
+    return g.layout == NN ? launch_bf16<256, 192, true, false, bf16_t, TBP_NARROW_KD, TBP_NARROW_RING>(p, 1, s)
+                          : launch_bf16<256, 192, true, true, bf16_t, TBP_NARROW_KD, TBP_NARROW_RING>(p, 1, s);
   if (g.ws && g.causal == CAUSAL_NONE && !g.delta && reinterpret_cast<uintptr_t>(g.ws) % 256 == 0) {
     const SplitPlan plan = gemm_split_plan(dtype, g.layout, g.M, g.N, g.K, g.out_f32, g.batch);
     if (plan.split > 1 && plan.bytes <= g.ws_bytes)
@@ -973,8 +977,8 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
     const long t192 = (long)((q.M + 255) / 256) * ((q.N + 191) / 192);
     if (rem <= 128 || !has_narrow || t192 > 256) return run(q, rem > 128);
     if (g.out_f32) return launch_bf16<256, 192, false, false, float, 32>(q, 1, s);
-    return g.layout == NN ? launch_bf16<256, 192, true, false, bf16_t, 64>(q, 1, s)
-                          : launch_bf16<256, 192, true, true, bf16_t, 64>(q, 1, s);
+    return g.layout == NN ? launch_bf16<256, 192, true, false, bf16_t, TBP_NARROW_KD, TBP_NARROW_RING>(q, 1, s)
+                          : launch_bf16<256, 192, true, true, bf16_t, TBP_NARROW_KD, TBP_NARROW_RING>(q, 1, s);
   };
   if (big && g.batch == 1 && g.causal == CAUSAL_NONE && tiles_big > 256 && rem != 0 && (rem <= 128 || (has_narrow && rem <= 192))) {
     const long whole = tiles_big - rem;

@@ -141,7 +141,9 @@ def test_rmsnorm_fwd_and_p1(dtype, rows, d):
 
 
 @pytest.mark.parametrize("dtype,rows,d", [("bf16", 4096, 4096), ("bf16", 2051, 5120), ("bf16", 515, 8192), ("bf16", 300, 2048),
-                                          ("bf16", 3, 264), ("f32", 130, 1028)])
+                                          ("bf16", 3, 264), ("f32", 130, 1028),
+                                          # widths that leave lanes of the 8-wave rows without a vector, one row only
+                                          ("bf16", 66, 2056), ("bf16", 9, 4104), ("bf16", 1, 4096)])
 def test_rmsnorm_p1_partial_rows_and_their_sum(dtype, rows, d):
     """The two halves of the RMSNorm backward as the stage runs them: backward-p1 leaves dx and the partial rows of the
     gain gradient, backward-p2 adds partial rows up; partial rows of two micro-batches stored one after the other are
