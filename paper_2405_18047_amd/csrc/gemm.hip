@@ -980,7 +980,17 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
     return g.layout == NN ? launch_bf16<256, 192, true, false, bf16_t, TBP_NARROW_KD, TBP_NARROW_RING>(q, 1, s)
                           : launch_bf16<256, 192, true, true, bf16_t, TBP_NARROW_KD, TBP_NARROW_RING>(q, 1, s);
   };
-  if (big && g.batch == 1 && g.causal == CAUSAL_NONE && tiles_big > 256 && rem != 0 && (rem <= 128 || (has_narrow && rem <= 192))) {
+  const bool defer = g.defer_rest && g.out_f32 && g.layout == TN && g.alpha == 1.f && !g.a_panel;
+  if (g.defer_rest) g.defer_rest->M = 0;
+  auto hold_back = [&](const GemmParams& q) {       // the remainder, for the caller's grouped launch
+    GroupedProduct& r = *g.defer_rest;
+    r.A = q.A; r.B = q.B; r.C = static_cast<float*>(q.C);
+    r.M = q.M; r.N = q.N; r.K = q.K;
+    r.lda = (int)q.lda; r.ldb = (int)q.ldb; r.ldc = (int)q.ldc;
+    r.accumulate = q.accumulate;
+  };
+  if (big && g.batch == 1 && g.causal == CAUSAL_NONE && tiles_big > 256 && rem != 0 &&
+      (defer || rem <= 128 || (has_narrow && rem <= 192))) {
     const long whole = tiles_big - rem;
     const size_t ce = g.out_f32 ? 4 : 2;
     GemmParams a = p, b = p;
@@ -994,6 +1004,7 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
         b.C = (char*)p.C + n0 * ce;
         if (p.R) b.R = (const char*)p.R + n0 * 2;
         hipError_t e = run(a, true);
+        if (defer) { hold_back(b); return e; }
         return e != hipSuccess ? e : run_rest(b);
       }
     } else {                                        // cut along M
@@ -1006,6 +1017,7 @@ hipError_t gemm(int dtype, const GemmArgs& g, hipStream_t s) {
         b.C = (char*)p.C + m0 * g.ldc * ce;
         if (p.R) b.R = (const char*)p.R + m0 * g.ldc * 2;
         hipError_t e = run(a, true);
+        if (defer) { hold_back(b); return e; }
         return e != hipSuccess ? e : run_rest(b);
       }
     }

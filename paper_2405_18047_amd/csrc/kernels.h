@@ -19,6 +19,7 @@ enum Causal {
 };
 constexpr int kCausalPad = 256;
 
+struct GroupedProduct;
 struct GemmArgs {
   int layout;            // Layout
   int M, N, K;
@@ -49,6 +50,12 @@ struct GemmArgs {
   // A[(m / kPanel) * a_panel + k * lda + m % kPanel] with lda == kPanel, so that the K x kPanel slab an output tile
   // contracts over is one contiguous stream.  0: plain [K, lda] matrix.  Such a product runs on kPanel-wide tiles.
   long a_panel;
+  // Weight-gradient products (TN layout, bf16 storage, fp32 C, alpha = 1) whose tiles do not fill whole rounds of the
+  // 256 compute units: when set, gemm() launches only the part of the output that makes whole rounds of large tiles
+  // and describes the remainder in *defer_rest (M = 0 there: nothing was held back) instead of launching it on
+  // smaller tiles.  The caller collects the remainders of several products and runs them as one gemm_tn_grouped
+  // launch, in which they fill rounds together.
+  GroupedProduct* defer_rest;
 };
 constexpr int kPanel = 128;
 // elements of one (sequence, head) entry of the fused attention's dS^T scratch, stored in such panels

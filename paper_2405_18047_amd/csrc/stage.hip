@@ -417,15 +417,19 @@ tbp_status run_p1(tbp_stage* st, int mb, int slot, const void* dy, void* dx, hip
   return TBP_OK;
 }
 
-// dW (=, +=) X^T dY over rows [row0, row0 + K) of the two slabs.
+// dW (=, +=) X^T dY over rows [row0, row0 + K) of the two slabs.  rests != nullptr: the part of the output that does
+// not make whole rounds of large tiles is not launched but appended to *rests, for one grouped launch at the end.
 tbp_status p2_product(tbp_stage* st, int layer, int xt, int dyt, int mb0, int K, float* dW, int accumulate,
-                      hipStream_t s) {
+                      hipStream_t s, std::vector<tbp::GroupedProduct>* rests = nullptr) {
   const Dims& c = st->c;
   const int M = (int)w_width(c, xt), N = (int)w_width(c, dyt);
   GemmArgs g = gemm_args(tbp::TN, M, N, K, st->wslab(layer, xt, mb0), M, st->wslab(layer, dyt, mb0), N, dW, N);
   g.out_f32 = 1;
   g.accumulate = accumulate;
+  tbp::GroupedProduct rest{};
+  if (rests) g.defer_rest = &rest;
   TBP_HIP(tbp::gemm(c.dtype, g, s));
+  if (rests && rest.M > 0) rests->push_back(rest);        // (capacity reserved at creation: no allocation here)
   return TBP_OK;
 }
 
@@ -462,11 +466,16 @@ tbp_status run_p2(tbp_stage* st, const int* mbs, int n, int mode, int accumulate
       TBP_HIP(tbp::gemm_tn_grouped(table.data(), (int)table.size(), s));
     }
   } else {
+    // K-concatenated bf16 products: one launch per weight for the whole rounds of large tiles (tiles that start in step
+    // share operand panels through the L2), and the remainders of all the stage's products together in one grouped
+    // launch at the end, where they fill rounds with each other instead of each running a last, mostly empty round
+    std::vector<tbp::GroupedProduct>* rests = (mode == TBP_P2_KCONCAT && c.dtype == TBP_BF16) ? &st->grouped : nullptr;
+    if (rests) rests->clear();
     for (int l = 0; l < c.L; l++)
       for (const Prod& p : prods) {
         if (p.attn_only && !c.attn) continue;
         if (mode == TBP_P2_KCONCAT) {
-          tbp_status r = p2_product(st, l, p.x, p.dy, mbs[0], n * c.T, p.dw[l], accumulate, s);
+          tbp_status r = p2_product(st, l, p.x, p.dy, mbs[0], n * c.T, p.dw[l], accumulate, s, rests);
           if (r != TBP_OK) return r;
         } else {
           for (int i = 0; i < n; i++) {
@@ -475,6 +484,7 @@ tbp_status run_p2(tbp_stage* st, const int* mbs, int n, int mode, int accumulate
           }
         }
       }
+    if (rests && !rests->empty()) TBP_HIP(tbp::gemm_tn_grouped(rests->data(), (int)rests->size(), s));
   }
   if (c.literal) {
     // gain gradients from the stashed norm inputs and output derivatives (Section 3.1 treats a norm's gain like any

@@ -43,3 +43,18 @@ def test_work_is_conserved_and_memory_claims_hold():
     assert r.peak_pending_p2[0] == 1 and r.peak_pending_p2[-1] == n
     # a stage with free weight gradients gains nothing from deferring them
     assert sch.throughput_gain("1f1b-1", n, 1, 1, 0) == 1
+
+
+def test_bench_schedule_prediction_and_power_sampler_without_a_gpu():
+    """The host-side legs of the benchmark: with equal times the prediction equals Table 1's closed forms; with a
+    cheap p2 the gain shrinks towards 1; the power sampler reports nothing rather than failing where the GPU's sysfs
+    files do not exist."""
+    import bench
+    eq = bench.schedule_prediction(5.0, 5.0, 5.0)
+    assert eq["gain"] == eq["gain_equal_times_table1"]
+    cheap = bench.schedule_prediction(5.0, 5.0, 0.05)
+    for k, v in cheap["gain"].items():
+        assert 1.0 <= v < 1.01 and v < eq["gain"][k], k
+    with bench._PowerSampler() as smp:
+        pass
+    assert isinstance(smp.mhz, list) and isinstance(smp.watts, list)
