@@ -58,6 +58,8 @@ def main() -> int:
                     help="skip the CPU oracle leg (its timing and the live parity figure of one real-shape layer)")
     ap.add_argument("--no-parity-depth", action="store_true",
                     help="skip the 8-layer end-to-end comparison with the oracle (about a minute and a half of host time)")
+    ap.add_argument("--no-power-state", action="store_true",
+                    help="skip the extra p2 passes during which shader clock and socket power are sampled")
     ap.add_argument("--no-kernel-rates", action="store_true")
     ap.add_argument("--no-graph-replay", action="store_true")
     ap.add_argument("--no-loop-compare", action="store_true",
@@ -207,7 +209,7 @@ def main() -> int:
             t = json.load(fh).get(shape.name)
         if t:
             out["roofline"]["traffic"] = t["hbm_bytes_per_launch"]
-    if not args.probe:
+    if not args.no_power_state:
         out["roofline"]["power_state_during_p2"] = p2_power_state(st, tbp, torch, xs, dys, x_out, dx_out, M)
     out["schedule_prediction"] = schedule_prediction(statistics.median(fwd_ms) / M, statistics.median(p1_ms),
                                                      statistics.median(p2_ms) / M)
