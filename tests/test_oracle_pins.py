@@ -374,3 +374,13 @@ def test_planted_mistakes_are_caught(tiny_shape, monkeypatch, mutation):
     worst = max(_relerr(dxs[m], mdx[m]) for m in range(len(xs)))
     worst = max([worst] + [_relerr(grads[k][l], mgr[k][l]) for k in grads for l in range(len(grads[k]))])
     assert worst > 1e-6
+
+
+def test_bf16_storage_floor_analysis_runs_and_orders_of_magnitude():
+    """The analysis script beside the oracle (fp64 arithmetic, bf16 rounding at the storage points of a bf16
+    implementation) at a reduced sequence length: the floor of one 7B-shaped layer is several 1e-3, far above fp64
+    noise and below the 2e-2 tolerance that a single layer has to meet."""
+    from oracle.bf16_storage_floor import storage_floor
+    e = storage_floor(1, 64)
+    assert set(e) >= {"x_out", "dx", "dw_qkv[0]", "dw_o[0]", "dg1[0]", "dw_gu[0]", "dw_d[0]", "dg2[0]"}
+    assert all(1e-3 < v < 2e-2 for v in e.values()), e
