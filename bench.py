@@ -211,6 +211,7 @@ def main() -> int:
             out["roofline"]["traffic"] = t["hbm_bytes_per_launch"]
     if not args.no_power_state:
         out["roofline"]["power_state_during_p2"] = p2_power_state(st, tbp, torch, xs, dys, x_out, dx_out, M)
+        out["power_state_during_p1"] = p2_power_state(st, tbp, torch, xs, dys, x_out, dx_out, M, reps=2, phase="p1")
     out["schedule_prediction"] = schedule_prediction(statistics.median(fwd_ms) / M, statistics.median(p1_ms),
                                                      statistics.median(p2_ms) / M)
     if not args.no_graph_replay:
@@ -729,21 +730,30 @@ class _PowerSampler:
         self._thread.join()
 
 
-def p2_power_state(st, tbp, torch, xs, dys, x_out, dx_out, M, reps=3) -> dict:
-    """Shader clock and socket power sampled from sysfs while K-concatenated p2 calls run (outside the timed steps):
-    the matrix-bound kernels run under the chip's power management, so the clock they sustain is part of the record."""
+def p2_power_state(st, tbp, torch, xs, dys, x_out, dx_out, M, reps=3, phase="p2") -> dict:
+    """Shader clock and socket power sampled from sysfs while K-concatenated p2 calls run (or, phase="p1", while the
+    backward-p1 calls of all micro-batches run), outside the timed steps: the matrix-bound kernels run under the
+    chip's power management, so the clock they sustain is part of the record."""
     mhz, watts, ms = [], [], []
     for _ in range(reps):
         for m in range(M):
             st.forward(m, xs[m], x_out)
-        for m in range(M):
-            st.backward_p1(m, dys[m], dx_out)
+        if phase == "p2":
+            for m in range(M):
+                st.backward_p1(m, dys[m], dx_out)
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         with _PowerSampler() as smp:
             a.record()
-            st.backward_p2(range(M), tbp.TBP_P2_KCONCAT, accumulate=False)
+            if phase == "p2":
+                st.backward_p2(range(M), tbp.TBP_P2_KCONCAT, accumulate=False)
+            else:
+                for m in range(M):
+                    st.backward_p1(m, dys[m], dx_out)
             b.record()
+            torch.cuda.synchronize()
+        if phase != "p2":
+            st.backward_p2(range(M), tbp.TBP_P2_KCONCAT, accumulate=False)
             torch.cuda.synchronize()
         ms.append(a.elapsed_time(b))
         mhz += smp.mhz[1:]            # (the first sample may predate the first kernel)
@@ -753,7 +763,7 @@ def p2_power_state(st, tbp, torch, xs, dys, x_out, dx_out, M, reps=3) -> dict:
     mean = lambda v: round(sum(v) / len(v), 1) if v else None
     return {"available": True, "sclk_mhz_mean": mean(mhz), "sclk_mhz_min": min(mhz) if mhz else None,
             "sclk_mhz_max": max(mhz) if mhz else None, "sclk_mhz_nominal": 2400.0, "socket_watts_mean": mean(watts),
-            "socket_watts_max": max(watts) if watts else None, "samples": len(mhz), "p2_ms": round(statistics.median(ms), 3),
+            "socket_watts_max": max(watts) if watts else None, "samples": len(mhz), f"{phase}_ms": round(statistics.median(ms), 3),
             "source": "sysfs pp_dpm_sclk (current level) and hwmon power1_input, sampled every ~4 ms on a host thread"}
 
 

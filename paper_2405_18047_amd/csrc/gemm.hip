@@ -445,7 +445,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmParams& p, int tm_i, in
     // what the strip needs from memory (old C for +=, residual or probabilities) is requested for the whole strip
     // first, so the stores below wait for one memory latency per strip instead of one per row group
     constexpr int NIT = NVEC / 64;                            // stores per strip, and per request batch:
-    constexpr int GRP = NIT <= 8 ? NIT : (NIT % 8 == 0 ? 8 : (NIT % 6 == 0 ? 6 : 4));
+    constexpr int GRP = NIT <= 8 ? NIT : (NIT % 8 == 0 ? 8 : (NIT % 6 == 0 ? 6 : (NIT % 5 == 0 ? 5 : 4)));
     static_assert(NIT % GRP == 0, "request batches must tile the strip");
     const bool need_pre = (sizeof(OutT) == 4) ? false : (R != nullptr);   // (fp32 += reads its old value in place)
     __builtin_amdgcn_sched_barrier(0);      // keep the next strip's requests from being hoisted over this one

@@ -34,6 +34,8 @@ GEMM_SHAPES = [  # (M, N, K): several tiles plus ragged tails in every dimension
     (2040, 5128, 328), (1024, 11016, 200),
     # 432 large tiles: one whole round + 176, the rest of which runs on 256 x 192 tiles (cut along N, and along M)
     (4096, 6904, 264), (6904, 4096, 136),
+    # [2048, 5120]: one full round of 128 x 320 tiles; ragged in M, N and K
+    (2048, 5120, 328), (2040, 5112, 264),
 ]
 
 
