@@ -745,6 +745,8 @@ static NormPlan norm_plan(int dtype, int d) {
     // up to 4096 columns one vector per lane and two rows per 1024-thread workgroup; wider rows two vectors per lane
     // and one row per 512-thread workgroup (two vectors per lane in 1024 threads do not fit the register file)
     if (wc > 4) return NormPlan{1, 8, wc <= 8 ? TBP_RING_NW1 / 8 : 1};
+    // 1024 < columns <= 2048: the same kernel with 4 waves per row, four rows per 1024-thread workgroup
+    if (wc > 2) return NormPlan{1, 4, 4};
     return NormPlan{0, 1, 8};
   }
   const int wpr = wc <= 4 ? 1 : wc <= 8 ? 2 : wc <= 16 ? 4 : 8;
@@ -773,7 +775,12 @@ static hipError_t rmsnorm_p1_w(int rows, int d, float eps, const T* dy, const T*
 
 template <typename T, bool GAIN_ONLY>
 static hipError_t rmsnorm_p1_ring(int rows, int d, float eps, const T* dy, const T* x, const T* g, const T* resid, T* dx,
-                                  float* partials, int nblk, hipStream_t s) {
+                                  float* partials, int nblk, int wpr, hipStream_t s) {
+  if (wpr == 4) {       // at most 256 vectors per row: one per lane
+    const size_t smem4 = (4 * 16 + (size_t)d) * sizeof(float);
+    hipLaunchKernelGGL((rmsnorm_p1_ring_kernel<T, 1, 4, GAIN_ONLY, 16, TBP_RING_PD1>), dim3(nblk), dim3(1024), smem4, s, rows, d, eps, dy, x, g, resid, dx, partials);
+    return hipGetLastError();
+  }
   constexpr int WPR = 8;
   const int c = (d / Vec<T>::N + 64 * WPR - 1) / (64 * WPR);      // vectors per lane
   if (c > 2) return hipErrorInvalidValue;
@@ -794,7 +801,7 @@ static hipError_t rmsnorm_rows_t(int dtype, int rows, int d, float eps, const vo
   const NormPlan pl = norm_plan(dtype, d);
   const int nblk = rmsnorm_partial_rows(dtype, rows, d);
   if constexpr (sizeof(T) == 2) {
-    if (pl.kind == 1) return rmsnorm_p1_ring<T, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, partials, nblk, s);
+    if (pl.kind == 1) return rmsnorm_p1_ring<T, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, partials, nblk, pl.wpr, s);
   }
   switch (pl.wpr) {
     case 1: return rmsnorm_p1_w<T, 1, GAIN_ONLY>(rows, d, eps, DY, X, G, RS, DX, partials, nblk, s);
